@@ -1,0 +1,269 @@
+/*
+ * esp.h -- C ABI of the ESP (Embedding-Space Probing) speculate-and-verify decode step
+ * for MI355X (gfx950).  Plain pointers and sizes only; no C++ or framework types.
+ *
+ * One decode step (paper Sec. 3.3, Fig. 1 right) is four calls on one stream:
+ *
+ *   esp_tree_forward      forward of [last accepted token | draft-tree tokens | mask tokens]
+ *                         against the KV cache under the tree attention mask, LM head and
+ *                         argmax at the tree rows                       (Sec. 2, Sec. 3.3, App. C/E)
+ *   esp_verify_accept     lossless longest-accepted-path check, bonus token, KV commit
+ *                                                                       (Sec. 2 Eq. 3, Sec. 3.3, Sec. 4)
+ *   esp_mask_topk         LM head + vocabulary softmax + Top-K' at the mask rows aligned to the
+ *                         accepted position                             (Sec. 2 Eq. 2, Sec. 3.3)
+ *   esp_build_prune_tree  pruning rule and dynamic tree construction -> next block
+ *                                                                       (Sec. 3.4 Alg. 1, Sec. 3.5, App. C)
+ *
+ * Conventions
+ *  - "device" = pointer into GPU memory owned by the caller; "host" = ordinary host memory.
+ *    The library never allocates or frees device memory and never keeps a caller pointer
+ *    beyond the call, except the weight pointers handed to esp_create (kept until esp_destroy)
+ *    and the workspace.
+ *  - Every call enqueues its kernels on the ctx stream and returns without synchronising,
+ *    except where stated.  The return value reports what the host can check (null pointers,
+ *    shapes, capacities known on the host).  Conditions only the device can see (a sequence
+ *    whose length exceeds the host's bound or its capacity, a malformed tree) set a sticky
+ *    device status word, read with esp_last_device_status(); the offending work is skipped,
+ *    never executed out of bounds.
+ *  - No entry point throws or aborts.
+ *  - Matrices are row-major [out_features, in_features] in the model dtype.
+ *  - Rows: a block holds `batch` sequences, sequence b owning rows
+ *    [b*rows_per_seq, b*rows_per_seq + n_rows[b]).  Within a sequence rows 0..n_nodes-1 are
+ *    tree nodes in (depth, creation) order, row 0 the last accepted token; mask rows follow
+ *    (Fig. 3).  ESP_LAYOUT_PER_NODE: node a owns mask rows n_nodes + a*k + (j-1), j = 1..k,
+ *    so n_rows = (k+1) n_nodes (block complexity, Sec. 3.3).  ESP_LAYOUT_ROOT_CHAIN: only the
+ *    root owns a chain, n_rows = n_nodes + k.
+ */
+#ifndef ESP_H_
+#define ESP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct esp_ctx esp_ctx; /* opaque; host object, owns nothing on the device */
+
+typedef enum {
+  ESP_OK = 0,
+  ESP_EINVAL = 1,    /* null pointer or value out of range */
+  ESP_ESHAPE = 2,    /* shape the kernels do not support */
+  ESP_ECAPACITY = 3, /* rows / batch / length beyond what ctx or workspace was created for */
+  ESP_EDTYPE = 4,
+  ESP_EDEVICE = 5,   /* a HIP call failed */
+  ESP_ESTATE = 6
+} esp_status;
+
+typedef enum { ESP_F32 = 0, ESP_BF16 = 1 } esp_dtype;
+
+enum { ESP_LAYOUT_PER_NODE = 0, ESP_LAYOUT_ROOT_CHAIN = 1 };
+
+enum {
+  ESP_MAX_MASKS = 8,         /* k */
+  ESP_MAX_ROWS_PER_SEQ = 1024,
+  ESP_MAX_TOPK = 32,         /* K' */
+  ESP_MAX_TREE_NODES = 256,  /* B */
+  ESP_KV_BLOCK = 64          /* V-cache slot blocking, see esp_kv */
+};
+
+/* bits of the device status word */
+enum {
+  ESP_DEV_LEN_OVER_BOUND = 1,  /* kv.len[b] + n_rows[b] exceeds kv.len_bound or seq capacity */
+  ESP_DEV_BAD_TREE = 2,        /* parent not before child, n_nodes/n_rows out of range      */
+  ESP_DEV_BAD_TOKEN = 4        /* token id outside the vocabulary                            */
+};
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+  float rope_theta; /* rotary base; pairs (i, i + head_dim/2) turn by pos * theta^(-2i/head_dim) */
+  float rms_eps;
+  int32_t qk_norm;  /* 1: per-head RMSNorm over head_dim on q and k before the rotation */
+  int32_t dtype;    /* esp_dtype of weights, KV cache, mask embeddings and hidden_out */
+} esp_model_desc;
+
+/* Weights: the arrays of per-layer pointers are HOST arrays of n_layers DEVICE pointers. */
+typedef struct {
+  const void *embed;             /* [vocab, d_model]                                   */
+  const void *lm_head;           /* [vocab, d_model] (untied)                          */
+  const void *final_norm;        /* [d_model]                                          */
+  const void *const *wqkv;       /* [(n_q + 2 n_kv) * head_dim, d_model]: q, k, v rows */
+  const void *const *wo;         /* [d_model, n_q * head_dim]                          */
+  const void *const *w_gate_up;  /* [2 d_ff, d_model]: gate rows then up rows          */
+  const void *const *w_down;     /* [d_model, d_ff]                                    */
+  const void *const *norm_attn;  /* [d_model]                                          */
+  const void *const *norm_mlp;   /* [d_model]                                          */
+  const void *const *q_norm;     /* [head_dim], NULL unless qk_norm                    */
+  const void *const *k_norm;     /* [head_dim], NULL unless qk_norm                    */
+} esp_weights;
+
+/* KV cache pool (device, model dtype), shared by the sequences of a batch.
+ *   k: [n_layers][n_kv_heads][capacity][head_dim]
+ *   v: [n_layers][n_kv_heads][capacity / 64][head_dim][64]   (slot-blocked, transposed inside
+ *      a block of 64 slots, so that a tile of V arrives with slots contiguous per feature)
+ * Sequence b owns slots [base[b], base[b] + seq_cap[b]); base[b] is a multiple of 64.
+ * Slots [0, len[b]) of a sequence hold committed tokens; a forward writes the block's rows at
+ * len[b] + row (scratch until committed). */
+typedef struct {
+  void *k, *v;             /* device */
+  int32_t *len;            /* device [batch]; advanced by esp_verify_accept                   */
+  const int32_t *base;     /* device [batch]                                                  */
+  const int32_t *seq_cap;  /* device [batch]                                                  */
+  int64_t capacity;        /* host: slots per (layer, kv head) in the pool, multiple of 64    */
+  int32_t len_bound;       /* host: upper bound of len[b] over the batch for this call; sizes */
+                           /* the attention launch (the kernels read the true len on device)  */
+} esp_kv;
+
+/* One forward block.  Scalars are host values; arrays are device memory sized for
+ * batch * rows_per_seq rows, written by esp_build_prune_tree / esp_block_from_tree. */
+typedef struct {
+  int32_t batch;
+  int32_t rows_per_seq; /* row stride of a sequence, <= ESP_MAX_ROWS_PER_SEQ               */
+  int32_t k_masks;      /* k, 0..ESP_MAX_MASKS                                              */
+  int32_t layout;
+  int32_t anc_words;    /* 64-bit words per ancestor bitset = ceil(rows_per_seq / 64)       */
+  int32_t *n_rows;      /* [batch]                                                          */
+  int32_t *n_nodes;     /* [batch]                                                          */
+  int32_t *tok;         /* [rows] token id of node rows, -1 on mask rows                    */
+  int32_t *parent;      /* [rows] tree parent row (in-sequence index), -1 for the root;     */
+                        /*        mask rows: the row before them in their chain             */
+  int32_t *depth;       /* [rows] position of a row = len[b] + depth (App. E)               */
+  int32_t *mask_j;      /* [rows] 0 for node rows, 1..k for mask rows                       */
+  int32_t *attach;      /* [rows] node row a mask row hangs on (node rows: themselves)      */
+  uint64_t *anc;        /* [rows][anc_words] bit c set: row may attend to block row c       */
+} esp_block;
+
+/* Parameters of the tree builder (Alg. 1; Sec. 3.5). */
+typedef struct {
+  int32_t B;            /* node budget including the root, <= ESP_MAX_TREE_NODES             */
+  int32_t k;            /* mask tokens = maximum depth                                       */
+  int32_t K;            /* cap on children per expanded node (children = min(K, B - i))      */
+  int32_t expand_width; /* nodes expanded per depth: 1 = Top-1 expansion (App. C), <=0 = all */
+  int32_t prune_parent; /* drop a candidate equal to its parent's token (Sec. 3.5)           */
+  int32_t prune_last;   /* also drop the last generated token at depths >= 2                 */
+  int32_t layout;       /* layout of the block to write                                      */
+  int32_t static_widths[ESP_MAX_MASKS]; /* [K_1..K_k] fixed tree, no selection; all 0 = dynamic */
+} esp_tree_params;
+
+const char *esp_status_str(esp_status s);
+
+/* Workspace (device scratch for activations, split-K partials, attention partials, logits of
+ * the mask rows).  max_rows_per_seq and max_batch bound every later block; max_kv_len bounds
+ * kv.len_bound + rows_per_seq. */
+size_t esp_workspace_bytes(const esp_model_desc *m, int32_t max_batch, int32_t max_rows_per_seq,
+                           int64_t max_kv_len);
+
+/* Creates the host context.  `workspace` is device memory of at least esp_workspace_bytes(),
+ * 256-byte aligned, owned by the caller and used by every call until esp_destroy.  `stream` is a
+ * hipStream_t (NULL = the default stream).  Calls on one ctx must not overlap.
+ * Errors: EINVAL (null / non-positive sizes), ESHAPE (head_dim not in {64,128} for bf16 models,
+ * d_model or d_ff not a multiple of 64 for bf16, n_q_heads not a multiple of n_kv_heads, ...),
+ * ECAPACITY (workspace too small), EDTYPE. */
+esp_status esp_create(const esp_model_desc *m, const esp_weights *w, int32_t max_batch,
+                      int32_t max_rows_per_seq, int64_t max_kv_len, void *workspace,
+                      size_t workspace_bytes, void *stream, esp_ctx **out);
+esp_status esp_destroy(esp_ctx *ctx);
+
+/* Synchronises the stream and returns (and clears) the sticky device status bits. */
+esp_status esp_last_device_status(esp_ctx *ctx, int32_t *host_out);
+
+/* ---- the four calls of a step ------------------------------------------------------------ */
+
+/* Forward of all rows of `blk` (Sec. 3.3): h0 = embed[tok] on node rows, mask_embed[j-1] on mask
+ * rows (Sec. 3.1); per layer RMSNorm, QKV, optional QK-norm, rotary at position len[b]+depth,
+ * K/V of the rows written to cache slots len[b]+row, tree-masked grouped-query attention over
+ * cache slots [0,len[b]) plus the block rows in the row's ancestor bitset (App. C), output
+ * projection, SwiGLU MLP; final RMSNorm.
+ *   mask_embed  device [k_masks, d_model], model dtype
+ *   hidden_out  device [batch*rows_per_seq, d_model], model dtype: final-norm hidden states
+ *   node_argmax device [batch*rows_per_seq] int32: argmax over the vocabulary of the LM head at
+ *               node rows (lowest id on ties); entries of mask rows are left untouched
+ *   logits_dbg  NULL, or device [batch*rows_per_seq, vocab] fp32 receiving the LM-head logits of
+ *               every row (parity tests)
+ * Errors: EINVAL, ECAPACITY (batch/rows beyond ctx, len_bound + rows_per_seq > max_kv_len). */
+esp_status esp_tree_forward(esp_ctx *ctx, const esp_block *blk, const void *mask_embed,
+                            const esp_kv *kv, void *hidden_out, int32_t *node_argmax,
+                            float *logits_dbg);
+
+/* Greedy verification (Sec. 2 Eq. 3): starting at the root, a child is accepted iff its token
+ * equals node_argmax of its parent; the walk ends at the first miss at node n*; node_argmax[n*]
+ * is the bonus token (Sec. 4: tau counts accepted + bonus).  Then the K/V of the accepted rows are
+ * moved to slots len+1.. in path order (the root already sits at len) and len[b] += n_emit[b].
+ * Outputs (device): n_emit [batch]; emit_tok, accepted_row [batch][ESP_MAX_MASKS+1]
+ * (accepted_row[b][0] = 0, the root, then the accepted rows); star_row [batch] = n*. */
+esp_status esp_verify_accept(esp_ctx *ctx, const esp_block *blk, const int32_t *node_argmax,
+                             const esp_kv *kv, int32_t *n_emit, int32_t *emit_tok,
+                             int32_t *accepted_row, int32_t *star_row);
+
+/* Proposal (Sec. 2 Eq. 2; Sec. 3.3): LM head on the mask rows aligned to the accepted position,
+ * softmax over the full vocabulary in fp32, the Kp most probable tokens per row ordered by
+ * (probability descending, id ascending).  PER_NODE: rows mask(n*, i), i = 1..k.  ROOT_CHAIN:
+ * rows mask(root, a+i), i = 1..k-a, with a = n_emit-1 accepted tokens.
+ *   hidden   device: hidden_out of esp_tree_forward
+ *   topk_id  device [batch][k_masks][Kp] int32;  topk_p same shape fp32
+ *   n_lists  device [batch] int32: number of valid lists (depths the next tree may have)
+ *   logits_out NULL or device [batch][k_masks][vocab] fp32 (parity tests)
+ * Errors: EINVAL (Kp < 1 or > ESP_MAX_TOPK or > vocab). */
+esp_status esp_mask_topk(esp_ctx *ctx, const esp_block *blk, const int32_t *star_row,
+                         const int32_t *n_emit, const void *hidden, int32_t Kp, int32_t *topk_id,
+                         float *topk_p, int32_t *n_lists, float *logits_out);
+
+/* Pruning + dynamic tree (Alg. 1, Sec. 3.5): root = last emitted token with P = 1; for depth
+ * i = 1..n_lists the expanded nodes of depth i-1 (all of the current node set, or its
+ * expand_width most probable) take their first min(K, B-i) candidates of list i that survive the
+ * pruning rule, P(child) = P(parent) * p as one fp32 product; between depths the node set is the
+ * B-i most probable not-yet-used candidates; the tree is the root plus the B-1 most probable of
+ * all candidates (ties: earlier created first).  Writes every array of `next` for each sequence.
+ * Errors: EINVAL (B, k, K, Kp out of range; k != next->k_masks), ECAPACITY (rows of the tree
+ * exceed next->rows_per_seq). */
+esp_status esp_build_prune_tree(esp_ctx *ctx, const esp_tree_params *p, const int32_t *topk_id,
+                                const float *topk_p, int32_t Kp, const int32_t *n_lists,
+                                const int32_t *n_emit, const int32_t *emit_tok, esp_block *next);
+
+/* ---- stage-level and auxiliary entry points ----------------------------------------------- */
+
+/* Fills depth, mask rows, attach, mask_j, parent of mask rows, n_rows and the ancestor bitsets
+ * from blk->tok / blk->parent / blk->n_nodes of the node rows (already on the device). */
+esp_status esp_block_from_tree(esp_ctx *ctx, esp_block *blk);
+
+/* Mask vectors (Sec. 3.1): Eq. 4, m_i = mean of embed[prompt tokens] (fp32 accumulation), and
+ * Eq. 5, m <- m + lambda (embed[last emitted token of sequence 0] - m).  mask_embed: device
+ * [k, d_model] model dtype.  tokens: device int32. */
+esp_status esp_mask_mean(esp_ctx *ctx, const int32_t *tokens, int32_t n_tokens, int32_t k,
+                         void *mask_embed);
+esp_status esp_mask_ema(esp_ctx *ctx, const int32_t *n_emit, const int32_t *emit_tok, float lambda,
+                        int32_t k, void *mask_embed);
+
+/* Copies plain K/V rows [n_slots][n_kv_heads][head_dim] (model dtype, device) of one layer into /
+ * out of the cache layout at slots base + first_slot .. */
+esp_status esp_kv_store(esp_ctx *ctx, const esp_kv *kv, int32_t layer, int32_t seq_base,
+                        int32_t first_slot, int32_t n_slots, const void *k_rows, const void *v_rows);
+esp_status esp_kv_load(esp_ctx *ctx, const esp_kv *kv, int32_t layer, int32_t seq_base,
+                       int32_t first_slot, int32_t n_slots, void *k_rows, void *v_rows);
+
+/* C[M,N] (fp32, device) = A[M,K] * W[N,K]^T, A and W in `dtype` (device), on `stream`.
+ * bf16 needs N % 32 == 0 and K % 64 == 0.  `partials` is device scratch of
+ * esp_gemm_scratch_bytes(M,N,K) bytes (split-K partial sums; reduced in a fixed order). */
+size_t esp_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+esp_status esp_gemm(void *stream, int32_t dtype, const void *A, const void *W, float *C, int32_t M,
+                    int32_t N, int32_t K, void *partials, size_t partial_bytes);
+
+/* Tree-masked grouped-query attention of one layer (the kernel esp_tree_forward uses):
+ * q device [batch*rows_per_seq, n_q_heads, head_dim] model dtype, already rotated; K/V of the
+ * block rows already in the cache at len[b]+row; out same shape as q. */
+esp_status esp_attn_tree(esp_ctx *ctx, const esp_block *blk, const esp_kv *kv, int32_t layer,
+                         const void *q, void *out);
+
+/* Fused softmax + Top-K over `rows` fp32 logit rows of `vocab` entries (device): ids/probs
+ * [rows][Kp], ordered by (probability descending, id ascending).  `scratch`: device memory of
+ * esp_softmax_topk_scratch_bytes() bytes (per-chunk statistics and candidates). */
+size_t esp_softmax_topk_scratch_bytes(int32_t rows, int32_t vocab, int32_t Kp);
+esp_status esp_softmax_topk(void *stream, const float *logits, int32_t rows, int32_t vocab,
+                            int32_t Kp, int32_t *ids, float *probs, void *scratch,
+                            size_t scratch_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESP_H_ */

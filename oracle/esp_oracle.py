@@ -194,6 +194,28 @@ def block_inputs(model: Model, blk: Block, mask_embed: np.ndarray) -> np.ndarray
     return h
 
 
+def tree_attention(q: np.ndarray, k_cache, v_cache, k_blk, v_blk, visible: np.ndarray) -> np.ndarray:
+    """Tree-masked grouped-query attention of one layer (Sec. 3.3, App. C).  q [R, hq, hd]
+    (already rotated); k_cache/v_cache [L, hkv, hd] all visible to every row; k_blk/v_blk
+    [R, hkv, hd] of the block rows, row r seeing block row c iff visible[r, c].  Query head h
+    reads kv head h // (hq / hkv); scores scaled by 1/sqrt(hd); softmax with max subtraction."""
+    q = as_f64(q)
+    kc, vc, kb, vb = as_f64(k_cache), as_f64(v_cache), as_f64(k_blk), as_f64(v_blk)
+    R, hq, hd = q.shape
+    group = hq // kb.shape[1]
+    scale = 1.0 / np.sqrt(F64(hd))
+    att = np.zeros((R, hq, hd), dtype=F64)
+    for r in range(R):
+        cols = np.nonzero(visible[r])[0]
+        for hh in range(hq):
+            g = hh // group
+            keys = np.concatenate([kc[:, g, :], kb[cols, g, :]], axis=0)
+            vals = np.concatenate([vc[:, g, :], vb[cols, g, :]], axis=0)
+            p = softmax((keys @ q[r, hh]) * scale)
+            att[r, hh] = p @ vals
+    return att
+
+
 def tree_forward(model: Model, blk: Block, mask_embed, k_cache, v_cache, cache_len: int,
                  h0: Optional[np.ndarray] = None, want_logits_rows=None):
     """Forward all rows of `blk` in one call.  k_cache/v_cache: [n_layers][>=cache_len,
@@ -205,12 +227,10 @@ def tree_forward(model: Model, blk: Block, mask_embed, k_cache, v_cache, cache_l
     w = model.weights
     R, d, hd = blk.n_rows, model.d_model, model.head_dim
     hq, hkv = model.n_q_heads, model.n_kv_heads
-    group = hq // hkv
     h = block_inputs(model, blk, mask_embed) if h0 is None else as_f64(h0).copy()
     pos = cache_len + blk.depth
     k_new = np.zeros((model.n_layers, R, hkv, hd), dtype=F64)
     v_new = np.zeros((model.n_layers, R, hkv, hd), dtype=F64)
-    scale = 1.0 / np.sqrt(F64(hd))
     for l in range(model.n_layers):
         lw = w["layers"][l]
         x = rmsnorm(h, lw["norm_attn"], model.rms_eps)
@@ -223,17 +243,7 @@ def tree_forward(model: Model, blk: Block, mask_embed, k_cache, v_cache, cache_l
         q = rope(q, pos, model.rope_theta)
         kk = rope(kk, pos, model.rope_theta)
         k_new[l], v_new[l] = kk, vv
-        kc = as_f64(k_cache[l][:cache_len])
-        vc = as_f64(v_cache[l][:cache_len])
-        att = np.zeros((R, hq, hd), dtype=F64)
-        for r in range(R):
-            cols = np.nonzero(blk.visible[r])[0]
-            for hh in range(hq):
-                g = hh // group
-                keys = np.concatenate([kc[:, g, :], kk[cols, g, :]], axis=0)
-                vals = np.concatenate([vc[:, g, :], vv[cols, g, :]], axis=0)
-                p = softmax((keys @ q[r, hh]) * scale)
-                att[r, hh] = p @ vals
+        att = tree_attention(q, k_cache[l][:cache_len], v_cache[l][:cache_len], kk, vv, blk.visible)
         h = h + att.reshape(R, hq * hd) @ as_f64(lw["wo"]).T
         x = rmsnorm(h, lw["norm_mlp"], model.rms_eps)
         gate = x @ as_f64(lw["w_gate"]).T

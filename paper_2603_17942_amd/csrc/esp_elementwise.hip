@@ -1,0 +1,342 @@
+// Glue kernels of the ESP decode step: block assembly, norms, rotary + KV append, SwiGLU,
+// argmax, KV copies, mask-vector init / update.  All HBM-light; one pass over [rows, width].
+#include "esp_internal.h"
+
+#define ESP_DISPATCH(dtype, ...)          \
+  do {                                    \
+    if ((dtype) == ESP_F32) {             \
+      using T = float;                    \
+      __VA_ARGS__;                        \
+    } else {                              \
+      using T = bf16_t;                   \
+      __VA_ARGS__;                        \
+    }                                     \
+  } while (0)
+
+__device__ __forceinline__ bool seq_ok(const KvDev& kv, int seq, int n_rows) {
+  int L = kv.len[seq];
+  int base = kv.base[seq];
+  int cap = kv.seq_cap[seq];
+  return L >= 0 && L <= kv.len_bound && n_rows >= 0 && L + n_rows <= cap && base >= 0 && (base & 63) == 0 &&
+         (int64_t)base + cap <= kv.capacity;
+}
+
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+// ---- block assembly (Sec. 3.1, Sec. 3.3): h0 rows and the per-row rotary table ---------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(BlockDev b, KvDev kv, const T* __restrict__ embed,
+                                               const T* __restrict__ mask_embed, float* __restrict__ h, int d,
+                                               int vocab, float* __restrict__ rope_tab, int hd, float theta,
+                                               int32_t* status) {
+  const int row = blockIdx.x;
+  const int seq = row / b.rows_per_seq, r = row % b.rows_per_seq;
+  const int nr = b.n_rows[seq];
+  const bool ok = seq_ok(kv, seq, nr) && nr <= b.rows_per_seq;
+  if (r == 0 && threadIdx.x == 0 && !ok) atomicOr(status, ESP_DEV_LEN_OVER_BOUND);
+  const bool live = ok && r < nr;
+  const T* src = nullptr;
+  if (live) {
+    int j = b.mask_j[row];
+    if (j > 0) {
+      if (j <= b.k_masks) src = mask_embed + (size_t)(j - 1) * d;
+    } else {
+      int t = b.tok[row];
+      if (t < 0 || t >= vocab) {
+        if (threadIdx.x == 0) atomicOr(status, ESP_DEV_BAD_TOKEN);
+      } else {
+        src = embed + (size_t)t * d;
+      }
+    }
+  }
+  float* hr = h + (size_t)row * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) hr[i] = src ? to_f32(src[i]) : 0.f;
+  const int half = hd >> 1;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    // angle in double: positions reach 1e4..1e5 where an fp32 product loses the fraction
+    double pos = live ? (double)(kv.len[seq] + b.depth[row]) : 0.0;
+    double ang = pos * pow((double)theta, -2.0 * (double)i / (double)hd);
+    rope_tab[((size_t)row * half + i) * 2 + 0] = (float)cos(ang);
+    rope_tab[((size_t)row * half + i) * 2 + 1] = (float)sin(ang);
+  }
+}
+
+hipError_t launch_embed(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, const void* embed,
+                        const void* mask_embed, float* h, int d, int vocab, float* rope_tab, int hd,
+                        float theta, int32_t* status) {
+  int M = b.batch * b.rows_per_seq;
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_embed<T>, dim3(M), dim3(256), 0, st, b, kv, (const T*)embed,
+                                         (const T*)mask_embed, h, d, vocab, rope_tab, hd, theta, status));
+  return hipGetLastError();
+}
+
+// ---- residual add of split-K partials + RMSNorm ------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_residual_norm(float* __restrict__ h, const float* __restrict__ part,
+                                                       int splits, size_t split_stride, int d,
+                                                       const T* __restrict__ gain, float eps,
+                                                       T* __restrict__ xn) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  float* hr = h + row * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = hr[i];
+    for (int s = 0; s < splits; ++s) v += part[(size_t)s * split_stride + row * d + i];
+    hr[i] = v;
+    ss += v * v;
+  }
+  float tot = block_sum_256(ss, red);
+  float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) xn[row * d + i] = from_f32<T>(hr[i] * inv * to_f32(gain[i]));
+}
+
+hipError_t launch_residual_norm(hipStream_t st, int dtype, float* h, const float* part, int splits, int M,
+                                int d, const void* gain, float eps, void* xn_out) {
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_residual_norm<T>, dim3(M), dim3(256), 0, st, h, part, splits,
+                                         (size_t)M * d, d, (const T*)gain, eps, (T*)xn_out));
+  return hipGetLastError();
+}
+
+// ---- QKV epilogue: split-K reduce, optional per-head RMSNorm, rotary, KV append ----------------
+// one wave per (row, head); lane i < hd/2 owns the rotary pair (i, i + hd/2)
+template <typename T>
+__global__ __launch_bounds__(256) void k_qkv_post(BlockDev b, KvDev kv, int layer, const float* __restrict__ part,
+                                                  int splits, size_t split_stride, int hq, int hkv, int hd,
+                                                  int qk_norm, const T* __restrict__ qg, const T* __restrict__ kg,
+                                                  float eps, const float* __restrict__ rope_tab,
+                                                  T* __restrict__ q_out) {
+  const int row = blockIdx.y;
+  const int hidx = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int n_heads = hq + 2 * hkv;
+  if (hidx >= n_heads) return;
+  const int seq = row / b.rows_per_seq, r = row % b.rows_per_seq;
+  const int nr = b.n_rows[seq];
+  const bool live = seq_ok(kv, seq, nr) && nr <= b.rows_per_seq && r < nr;
+  const int half = hd >> 1;
+  const int ncol = n_heads * hd;
+  const bool act = lane < half;
+  float x0 = 0.f, x1 = 0.f;
+  if (act && live) {
+    size_t c0 = (size_t)row * ncol + (size_t)hidx * hd + lane;
+    for (int s = 0; s < splits; ++s) {
+      x0 += part[(size_t)s * split_stride + c0];
+      x1 += part[(size_t)s * split_stride + c0 + half];
+    }
+  }
+  if (hidx < hq + hkv) {
+    if (qk_norm) {
+      float ss = wave_sum(x0 * x0 + x1 * x1);
+      float inv = 1.0f / sqrtf(ss / (float)hd + eps);
+      const T* g = hidx < hq ? qg : kg;
+      if (act) {
+        x0 *= inv * to_f32(g[lane]);
+        x1 *= inv * to_f32(g[lane + half]);
+      }
+    }
+    if (!act) return;
+    float c = rope_tab[((size_t)row * half + lane) * 2 + 0];
+    float s = rope_tab[((size_t)row * half + lane) * 2 + 1];
+    float y0 = x0 * c - x1 * s;
+    float y1 = x1 * c + x0 * s;
+    if (hidx < hq) {
+      size_t o = ((size_t)row * hq + hidx) * hd + lane;
+      q_out[o] = from_f32<T>(y0);
+      q_out[o + half] = from_f32<T>(y1);
+    } else if (live) {
+      int kvh = hidx - hq;
+      int64_t slot = (int64_t)kv.base[seq] + kv.len[seq] + r;
+      T* kp = (T*)kv.k + kv_plane(layer, kvh, hkv, kv.capacity, hd);
+      kp[k_off(slot, lane, hd)] = from_f32<T>(y0);
+      kp[k_off(slot, lane + half, hd)] = from_f32<T>(y1);
+    }
+  } else if (act && live) {
+    int kvh = hidx - hq - hkv;
+    int64_t slot = (int64_t)kv.base[seq] + kv.len[seq] + r;
+    T* vp = (T*)kv.v + kv_plane(layer, kvh, hkv, kv.capacity, hd);
+    vp[v_off(slot, lane, hd)] = from_f32<T>(x0);
+    vp[v_off(slot, lane + half, hd)] = from_f32<T>(x1);
+  }
+}
+
+hipError_t launch_qkv_post(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer,
+                           const float* part, int splits, int M, int hq, int hkv, int hd, int qk_norm,
+                           const void* qg, const void* kg, float eps, const float* rope_tab, void* q_out) {
+  int n_heads = hq + 2 * hkv;
+  dim3 grid((n_heads + 3) / 4, M);
+  size_t stride = (size_t)M * n_heads * hd;
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_qkv_post<T>, grid, dim3(256), 0, st, b, kv, layer, part, splits,
+                                         stride, hq, hkv, hd, qk_norm, (const T*)qg, (const T*)kg, eps, rope_tab,
+                                         (T*)q_out));
+  return hipGetLastError();
+}
+
+// ---- SwiGLU over the fused gate/up GEMM output ---------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, int splits, size_t split_stride,
+                                                int dff, T* __restrict__ act, size_t total) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  size_t row = i / dff;
+  int j = (int)(i % dff);
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    const float* p = part + (size_t)s * split_stride + row * 2 * dff;
+    g += p[j];
+    u += p[dff + j];
+  }
+  float sg = g / (1.0f + expf(-g));
+  act[i] = from_f32<T>(sg * u);
+}
+
+hipError_t launch_swiglu(hipStream_t st, int dtype, const float* part, int splits, int M, int dff, void* act) {
+  size_t total = (size_t)M * dff;
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                                         part, splits, (size_t)M * 2 * dff, dff, (T*)act, total));
+  return hipGetLastError();
+}
+
+// ---- argmax over the vocabulary, lowest id on ties ------------------------------------------------
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, size_t row_stride,
+                                                const int32_t* __restrict__ row_map, int vocab,
+                                                int32_t* __restrict__ out, const int32_t* __restrict__ out_index) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int m = blockIdx.x;
+  const int dst = out_index ? out_index[m] : m;
+  if (dst < 0) return;
+  const size_t src = row_map ? (size_t)row_map[m] : (size_t)m;
+  const float* p = logits + src * row_stride;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < vocab; i += 256) {
+    float v = p[i];
+    if (v > best) { best = v; bi = i; }   // ascending i per thread: first maximum is kept
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(best, o, 64);
+    int oi = __shfl_xor(bi, o, 64);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+    out[dst] = bi == 0x7fffffff ? 0 : bi;
+  }
+}
+
+hipError_t launch_argmax(hipStream_t st, const float* logits, size_t row_stride, const int32_t* row_map,
+                         int n_rows_out, int vocab, int32_t* out, const int32_t* out_index) {
+  if (n_rows_out <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_argmax, dim3(n_rows_out), dim3(256), 0, st, logits, row_stride, row_map, vocab, out,
+                     out_index);
+  return hipGetLastError();
+}
+
+// gather lists for the LM head over node rows: logical row m = seq*max_nodes + i
+__global__ void k_node_rows(BlockDev b, int max_nodes, int32_t* a_rows, int32_t* out_rows) {
+  int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= b.batch * max_nodes) return;
+  int seq = m / max_nodes, i = m % max_nodes;
+  int nn = b.n_nodes[seq];
+  bool live = i < nn && nn <= b.n_rows[seq] && b.n_rows[seq] <= b.rows_per_seq;
+  a_rows[m] = seq * b.rows_per_seq + (live ? i : 0);
+  out_rows[m] = live ? seq * b.rows_per_seq + i : -1;
+}
+
+hipError_t launch_node_rows(hipStream_t st, const BlockDev& b, int max_nodes, int32_t* a_rows,
+                            int32_t* out_rows) {
+  int n = b.batch * max_nodes;
+  hipLaunchKernelGGL(k_node_rows, dim3((n + 255) / 256), dim3(256), 0, st, b, max_nodes, a_rows, out_rows);
+  return hipGetLastError();
+}
+
+// ---- plain rows <-> cache layout --------------------------------------------------------------------
+template <typename T>
+__global__ void k_kv_copy(KvDev kv, int layer, int n_kv, int hd, int seq_base, int first_slot, int n_slots,
+                          T* k_rows, T* v_rows, int to_cache) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)n_slots * n_kv * hd;
+  if (i >= total) return;
+  int d = (int)(i % hd);
+  int kvh = (int)((i / hd) % n_kv);
+  int s = (int)(i / ((size_t)hd * n_kv));
+  int64_t slot = (int64_t)seq_base + first_slot + s;
+  T* kp = (T*)kv.k + kv_plane(layer, kvh, n_kv, kv.capacity, hd);
+  T* vp = (T*)kv.v + kv_plane(layer, kvh, n_kv, kv.capacity, hd);
+  if (to_cache) {
+    kp[k_off(slot, d, hd)] = k_rows[i];
+    vp[v_off(slot, d, hd)] = v_rows[i];
+  } else {
+    k_rows[i] = kp[k_off(slot, d, hd)];
+    v_rows[i] = vp[v_off(slot, d, hd)];
+  }
+}
+
+hipError_t launch_kv_copy(hipStream_t st, int dtype, const KvDev& kv, int layer, int n_kv, int hd, int seq_base,
+                          int first_slot, int n_slots, void* k_rows, void* v_rows, int to_cache) {
+  size_t total = (size_t)n_slots * n_kv * hd;
+  if (total == 0) return hipSuccess;
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_kv_copy<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                                         kv, layer, n_kv, hd, seq_base, first_slot, n_slots, (T*)k_rows,
+                                         (T*)v_rows, to_cache));
+  return hipGetLastError();
+}
+
+// ---- mask vectors (Sec. 3.1 Eq. 4 and Eq. 5) -----------------------------------------------------------
+template <typename T>
+__global__ void k_mask_mean(const T* __restrict__ embed, const int32_t* __restrict__ tokens, int n, int k, int d,
+                            int vocab, T* __restrict__ mask_embed) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d) return;
+  float acc = 0.f;
+  for (int t = 0; t < n; ++t) {
+    int id = tokens[t];
+    if (id >= 0 && id < vocab) acc += to_f32(embed[(size_t)id * d + i]);
+  }
+  T v = from_f32<T>(acc / (float)n);
+  for (int j = 0; j < k; ++j) mask_embed[(size_t)j * d + i] = v;
+}
+
+hipError_t launch_mask_mean(hipStream_t st, int dtype, const void* embed, const int32_t* tokens, int n, int k,
+                            int d, int vocab, void* mask_embed) {
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_mean<T>, dim3((d + 255) / 256), dim3(256), 0, st, (const T*)embed,
+                                         tokens, n, k, d, vocab, (T*)mask_embed));
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void k_mask_ema(const T* __restrict__ embed, const int32_t* __restrict__ n_emit,
+                           const int32_t* __restrict__ emit_tok, float lambda, int k, int d, int vocab,
+                           T* __restrict__ mask_embed) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d) return;
+  int ne = n_emit[0];
+  if (ne < 1 || ne > ESP_MAX_MASKS + 1) return;
+  int id = emit_tok[ne - 1];
+  if (id < 0 || id >= vocab) return;
+  float e = to_f32(embed[(size_t)id * d + i]);
+  for (int j = 0; j < k; ++j) {
+    float m = to_f32(mask_embed[(size_t)j * d + i]);
+    mask_embed[(size_t)j * d + i] = from_f32<T>(m + lambda * (e - m));
+  }
+}
+
+hipError_t launch_mask_ema(hipStream_t st, int dtype, const void* embed, const int32_t* n_emit,
+                           const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed) {
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_ema<T>, dim3((d + 255) / 256), dim3(256), 0, st, (const T*)embed,
+                                         n_emit, emit_tok, lambda, k, d, vocab, (T*)mask_embed));
+  return hipGetLastError();
+}

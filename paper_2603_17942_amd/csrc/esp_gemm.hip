@@ -1,0 +1,268 @@
+// Dense projections of the decoder: out[s][M][N] (fp32 partial sums over split s) = A[M,K] * W[N,K]^T.
+//
+// bf16 path (the 8B-class workloads): M is the number of block rows (tens to hundreds) while W is
+// hundreds of MB per layer, so the kernel is a weight streamer.  Each wave owns NB blocks of 32
+// weight rows and reads them straight from HBM into the MFMA B-operand registers, 64 contiguous
+// bytes per lane and K-chunk, through a register ring that keeps several chunks in flight; no LDS
+// hop for the weights.  The activations (L2 resident) are staged once per workgroup in LDS and
+// shared by its four waves.  v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+// The order of k inside one MFMA is permuted identically for both operands (a lane takes its 8
+// values of step s from offset 32*(lane/32) + 8*s of the chunk), which leaves the dot product
+// unchanged and makes each lane's weight bytes contiguous.
+// Split-K (grid z) depends on (N, K) only, and partial sums are reduced by the consumer in split
+// order, so a row's result does not depend on how many other rows the block holds.
+//
+// fp32 path (tiny configuration): plain LDS-tiled FMA kernel with bounds checks.
+#include "esp_internal.h"
+
+namespace {
+
+constexpr int KC = 64;          // k per chunk
+constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
+
+template <int MT, int NB, int D>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
+                                                   const bf16_t* __restrict__ W, float* __restrict__ out, int M,
+                                                   int N, int K, int splits, int m_tiles, int n_tiles) {
+  extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
+  // XCD-aware logical id: consecutive hardware ids go to different XCDs, so give each XCD a
+  // contiguous range of tiles (tiles sharing weight rows then share an L2).
+  const int total = m_tiles * n_tiles * splits;
+  const int per_xcd = (total + 7) >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= total) return;
+  const int mi = logical % m_tiles;
+  const int ni = (logical / m_tiles) % n_tiles;
+  const int z = logical / (m_tiles * n_tiles);
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int lr = lane & 31, lg = lane >> 5;
+  const int m0 = mi * (MT * 32);
+  const int n0 = ni * (128 * NB) + wave * (32 * NB);
+
+  const int chunks = K / KC;
+  const int cps = (chunks + splits - 1) / splits;
+  const int c_begin = z * cps;
+  const int c_end = min(chunks, c_begin + cps);
+
+  // weight row pointers (clamped: out-of-range column blocks are computed but never stored)
+  const uint4* wp[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    int n = min(n0 + nb * 32 + lr, N - 1);
+    wp[nb] = reinterpret_cast<const uint4*>(W + (size_t)n * K + 32 * lg);
+  }
+  // activation staging: thread handles MT pieces of 16 B; piece p -> row p/8, 16-byte column p%8
+  const bf16_t* ap[MT];
+  int a_lds[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int p = tid + 256 * i;
+    int r = p >> 3, c16 = p & 7;
+    int m = min(m0 + r, M - 1);
+    if (a_rows) m = max(a_rows[m], 0);
+    ap[i] = A + (size_t)m * K + c16 * 8;
+    a_lds[i] = r * A_ROW_BYTES + c16 * 16;
+  }
+  const int a_buf_bytes = MT * 32 * A_ROW_BYTES;
+
+  f32x16_t acc[MT][NB];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  uint4 wreg[D][NB][4];
+  uint4 areg[MT];
+
+  // prologue: weights of the first D chunks, activations of the first chunk
+#pragma unroll
+  for (int u = 0; u < D; ++u) {
+    int c = c_begin + u;
+    if (c < c_end) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)c * (KC * 2 / 16) + s];
+    }
+  }
+  if (c_begin < c_end) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) areg[i] = *reinterpret_cast<const uint4*>(ap[i] + (size_t)c_begin * KC);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) *reinterpret_cast<uint4*>(lds + a_lds[i]) = areg[i];
+  }
+  __syncthreads();
+
+  for (int cb = c_begin; cb < c_end; cb += D) {
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+      const int c = cb + u;
+      if (c < c_end) {   // uniform over the workgroup
+        const int buf = (c - c_begin) & 1;
+        const bool more = c + 1 < c_end;
+        {
+          const int cn = more ? c + 1 : c;
+#pragma unroll
+          for (int i = 0; i < MT; ++i)
+            areg[i] = *reinterpret_cast<const uint4*>(ap[i] + (size_t)cn * KC);
+        }
+        const unsigned char* abase = lds + buf * a_buf_bytes + lr * A_ROW_BYTES + 64 * lg;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+          for (int i = 0; i < MT; ++i) {
+            bf16x8_t af = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES + 16 * s);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+              bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, wreg[u][nb][s]);
+              acc[i][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[i][nb], 0, 0, 0);
+            }
+          }
+        }
+        // refill this ring slot with the chunk D ahead
+        if (c + D < c_end) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)(c + D) * (KC * 2 / 16) + s];
+        }
+        {
+#pragma unroll
+          for (int i = 0; i < MT; ++i)
+            *reinterpret_cast<uint4*>(lds + (buf ^ 1) * a_buf_bytes + a_lds[i]) = areg[i];
+        }
+        __syncthreads();
+      }
+    }
+  }
+
+  // epilogue: lane holds column n, rows 8*(v/4) + 4*lg + v%4 of each 32x32 tile
+  float* o = out + (size_t)z * M * N;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int n = n0 + nb * 32 + lr;
+    if (n0 + nb * 32 < N) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int m = m0 + i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+          if (m < M) o[(size_t)m * N + n] = acc[i][nb][v];
+        }
+      }
+    }
+  }
+}
+
+// ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
+__global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, const int32_t* __restrict__ a_rows,
+                                                  const float* __restrict__ W, float* __restrict__ out, int M,
+                                                  int N, int K) {
+  __shared__ float As[16][65];
+  __shared__ float Ws[16][65];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      int r = i >> 4, kk = i & 15;
+      int m = m0 + r, n = n0 + r, k = k0 + kk;
+      float av = 0.f, wv = 0.f;
+      if (m < M && k < K) {
+        int pm = a_rows ? max(a_rows[m], 0) : m;
+        av = A[(size_t)pm * K + k];
+      }
+      if (n < N && k < K) wv = W[(size_t)n * K + k];
+      As[kk][r] = av;
+      Ws[kk][r] = wv;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) out[(size_t)m * N + n] = acc[i][j];
+    }
+}
+
+template <int MT, int NB>
+hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
+                       int N, int K, const GemmPlan& p) {
+  constexpr int D = 4;
+  int total = p.m_tiles * p.n_tiles * p.splits;
+  int per_xcd = (total + 7) / 8;
+  size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A, a_rows,
+                     (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+GemmPlan gemm_plan(int dtype, int M, int N, int K) {
+  GemmPlan p;
+  if (dtype == ESP_F32) {
+    p.splits = 1; p.mt = 2; p.nb = 2; p.m_tiles = (M + 63) / 64; p.n_tiles = (N + 63) / 64;
+    return p;
+  }
+  // split-K from (N, K) only: aim at >= 256 workgroups of 128 columns, at least 8 chunks each
+  int cols128 = (N + 127) / 128;
+  int s = (256 + cols128 - 1) / cols128;
+  int max_s = K / (KC * 8);
+  if (max_s < 1) max_s = 1;
+  if (s > max_s) s = max_s;
+  if (s > 8) s = 8;
+  if (s < 1) s = 1;
+  p.splits = s;
+  int tiles32 = (M + 31) / 32;
+  if (tiles32 <= 4) {
+    p.mt = tiles32; p.nb = 1; p.m_tiles = 1;
+  } else {
+    p.nb = 2;
+    p.m_tiles = (tiles32 + 4) / 5;
+    p.mt = (tiles32 + p.m_tiles - 1) / p.m_tiles;
+  }
+  p.n_tiles = (N + 128 * p.nb - 1) / (128 * p.nb);
+  return p;
+}
+
+hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
+                       float* out, int M, int N, int K, const GemmPlan& p) {
+  if (M <= 0) return hipSuccess;
+  if (dtype == ESP_F32) {
+    hipLaunchKernelGGL(k_gemm_f32, dim3(p.n_tiles, p.m_tiles), dim3(256), 0, st, (const float*)A, a_rows,
+                       (const float*)W, out, M, N, K);
+    return hipGetLastError();
+  }
+#define ESP_GEMM_CASE(MT_, NB_) \
+  if (p.mt == MT_ && p.nb == NB_) return launch_bf16<MT_, NB_>(st, A, a_rows, W, out, M, N, K, p);
+  ESP_GEMM_CASE(1, 1)
+  ESP_GEMM_CASE(2, 1)
+  ESP_GEMM_CASE(3, 1)
+  ESP_GEMM_CASE(4, 1)
+  ESP_GEMM_CASE(1, 2)
+  ESP_GEMM_CASE(2, 2)
+  ESP_GEMM_CASE(3, 2)
+  ESP_GEMM_CASE(4, 2)
+  ESP_GEMM_CASE(5, 2)
+#undef ESP_GEMM_CASE
+  return hipErrorInvalidValue;
+}

@@ -1,0 +1,148 @@
+// Internal declarations shared by the HIP sources of libesp_hip.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "esp.h"
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+#define ESP_WAVE 64
+
+// ---- element conversion -----------------------------------------------------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- KV cache addressing (see esp_kv in esp.h) --------------------------------------------
+// K: [layer][kv_head][capacity][hd]; V: [layer][kv_head][capacity/64][hd][64]
+__host__ __device__ __forceinline__ size_t kv_plane(int layer, int kvh, int n_kv, int64_t cap, int hd) {
+  return ((size_t)layer * n_kv + kvh) * (size_t)cap * hd;
+}
+__host__ __device__ __forceinline__ size_t k_off(int64_t slot, int d, int hd) {
+  return (size_t)slot * hd + d;
+}
+__host__ __device__ __forceinline__ size_t v_off(int64_t slot, int d, int hd) {
+  return ((size_t)(slot >> 6) * hd + d) * 64 + (slot & 63);
+}
+
+// ---- GEMM -----------------------------------------------------------------------------------
+struct GemmPlan {
+  int splits;        // split-K factor; depends on (N, K) only, never on M
+  int mt;            // 32-row MFMA tiles per workgroup
+  int nb;            // 32-column blocks per wave
+  int m_tiles;       // workgroup tiles along M
+  int n_tiles;       // workgroup tiles along N
+};
+GemmPlan gemm_plan(int dtype, int M, int N, int K);
+inline size_t gemm_out_elems(const GemmPlan& p, int M, int N) { return (size_t)p.splits * M * N; }
+// out: fp32 [splits][M][N].  a_rows (device, may be null): physical row of A for logical row m.
+hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
+                       float* out, int M, int N, int K, const GemmPlan& p);
+
+// ---- elementwise / glue (esp_elementwise.hip) ----------------------------------------------
+struct BlockDev {   // device-side view of esp_block + esp_kv scalars, passed by value
+  int batch, rows_per_seq, k_masks, layout, anc_words;
+  const int32_t *n_rows, *n_nodes, *tok, *parent, *depth, *mask_j, *attach;
+  const uint64_t* anc;
+};
+struct KvDev {
+  void *k, *v;
+  int32_t* len;
+  const int32_t *base, *seq_cap;
+  int64_t capacity;
+  int len_bound;
+};
+
+hipError_t launch_embed(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, const void* embed,
+                        const void* mask_embed, float* h, int d, int vocab, float* rope_tab, int hd,
+                        float theta, int32_t* status);
+hipError_t launch_residual_norm(hipStream_t st, int dtype, float* h, const float* part, int splits, int M,
+                                int d, const void* gain, float eps, void* xn_out);
+hipError_t launch_qkv_post(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer,
+                           const float* part, int splits, int M, int hq, int hkv, int hd, int qk_norm,
+                           const void* qg, const void* kg, float eps, const float* rope_tab, void* q_out);
+hipError_t launch_swiglu(hipStream_t st, int dtype, const float* part, int splits, int M, int dff, void* act);
+hipError_t launch_argmax(hipStream_t st, const float* logits, size_t row_stride, const int32_t* row_map,
+                         int n_rows_out, int vocab, int32_t* out, const int32_t* out_index);
+hipError_t launch_node_rows(hipStream_t st, const BlockDev& b, int max_nodes, int32_t* a_rows, int32_t* out_rows);
+hipError_t launch_kv_copy(hipStream_t st, int dtype, const KvDev& kv, int layer, int n_kv, int hd,
+                          int seq_base, int first_slot, int n_slots, void* k_rows, void* v_rows, int to_cache);
+hipError_t launch_mask_mean(hipStream_t st, int dtype, const void* embed, const int32_t* tokens, int n, int k,
+                            int d, int vocab, void* mask_embed);
+hipError_t launch_mask_ema(hipStream_t st, int dtype, const void* embed, const int32_t* n_emit,
+                           const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed);
+
+// ---- attention (esp_attn.hip) ------------------------------------------------------------------
+struct AttnPlan { int nsplit; int tiles_per_split; };
+AttnPlan attn_plan(int batch, int rows_per_seq, int hq, int hkv, int len_bound);
+size_t attn_partial_floats(int batch, int rows_per_seq, int hq, int hd, int nsplit);
+hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer, int hq,
+                       int hkv, int hd, const void* q, float* partials, const AttnPlan& p, void* out);
+
+// ---- softmax + top-k (esp_topk.hip) -----------------------------------------------------------
+size_t softmax_topk_scratch_floats(int rows, int vocab, int kp);
+hipError_t launch_softmax_topk(hipStream_t st, const float* logits, int rows, int vocab, int kp, int32_t* ids,
+                               float* probs, float* scratch);
+
+// ---- tree logic (esp_tree.hip) -------------------------------------------------------------------
+hipError_t launch_block_from_tree(hipStream_t st, int batch, int rows_per_seq, int k, int layout, int anc_words,
+                                  int32_t* n_rows, const int32_t* n_nodes, int32_t* tok, int32_t* parent,
+                                  int32_t* depth, int32_t* mask_j, int32_t* attach, uint64_t* anc,
+                                  int32_t* status);
+hipError_t launch_verify_accept(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv,
+                                const int32_t* node_argmax, int n_layers, int n_kv, int hd, int32_t* n_emit,
+                                int32_t* emit_tok, int32_t* accepted_row, int32_t* star_row, int32_t* status);
+hipError_t launch_mask_rows(hipStream_t st, const BlockDev& b, const int32_t* star_row, const int32_t* n_emit,
+                            int32_t* a_rows, int32_t* n_lists);
+hipError_t launch_build_tree(hipStream_t st, const esp_tree_params& p, int batch, const int32_t* topk_id,
+                             const float* topk_p, int kp, const int32_t* n_lists, const int32_t* n_emit,
+                             const int32_t* emit_tok, int rows_per_seq, int anc_words, int32_t* n_rows,
+                             int32_t* n_nodes, int32_t* tok, int32_t* parent, int32_t* depth, int32_t* mask_j,
+                             int32_t* attach, uint64_t* anc, int32_t* status);
+
+// ---- context --------------------------------------------------------------------------------------
+struct esp_ctx {
+  esp_model_desc m;
+  const void *embed, *lm_head, *final_norm;
+  std::vector<const void*> wqkv, wo, wgu, wdown, norm_attn, norm_mlp, q_norm, k_norm;
+  int max_batch, max_rows;
+  int64_t max_kv_len;
+  hipStream_t stream;
+  char* ws;
+  size_t ws_bytes;
+  // workspace partition
+  float* h;          // [Mmax][d] fp32 residual stream
+  void* xn;          // T [Mmax][d]
+  void* q;           // T [Mmax][hq*hd]
+  void* attn_out;    // T [Mmax][hq*hd]
+  void* act;         // T [Mmax][d_ff]
+  float* gemm_out;   // fp32 split-K partials of the largest layer GEMM
+  float* attn_part;  // attention split partials
+  float* rope_tab;   // [Mmax][hd/2][2] cos, sin
+  float* logits;     // fp32 [logits_rows][vocab]
+  float* topk_scratch;
+  int32_t* idx_a;    // [Mmax] gather rows
+  int32_t* idx_b;    // [Mmax]
+  int32_t* status;   // device status word
+  size_t gemm_out_floats, attn_part_floats, logits_rows;
+};
