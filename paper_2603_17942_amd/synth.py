@@ -164,54 +164,48 @@ def make_kv_fill(shape: ModelShape, length: int, seed: int = 5, device="cpu", st
 def make_random_tree(n_nodes: int, max_depth: int, vocab: int, seed: int = 7,
                      max_children: int = 8):
     """Random rooted tree in (depth, creation) row order: returns (tok[int32 n], parent[int32 n]).
-    parent[0] = -1; parents precede children; depth <= max_depth; sibling tokens distinct."""
-    idx = torch.arange(4 * n_nodes + 8, dtype=torch.int64)
-    r = _lsr(hash64(seed, 3, idx), 33).tolist()
-    toks = uniform_ints(4 * n_nodes + 8, vocab, seed, 4).tolist()
-    # grow level by level so that rows are sorted by depth
-    levels = [[0]]
-    parent = [-1]
-    tok = [toks[0]]
-    used = {0: set()}
-    cursor = 1
+    parent[0] = -1; parents precede children; depth <= max_depth; at most max_children children
+    per node; sibling tokens distinct."""
+    n_draw = 8 * n_nodes + 16
+    r = _lsr(hash64(seed, 3, torch.arange(n_draw, dtype=torch.int64)), 33).tolist()
+    toks = uniform_ints(n_draw, vocab, seed, 4).tolist()
+    cur = [0]
+
+    def draw():
+        cur[0] += 1
+        return r[cur[0] % n_draw]
+
+    tok, parent = [toks[0]], [-1]
+    prev_level = [0]
+    remaining = n_nodes - 1
     ti = 1
-    while len(parent) < n_nodes:
-        depth = len(levels)
-        if depth > max_depth:
-            # no room below: widen the deepest permitted level's parents instead
-            depth = max_depth
-        cand_parents = levels[depth - 1]
-        new_level = [] if depth == len(levels) else levels[depth]
-        want = max(1, min(n_nodes - len(parent), 1 + r[cursor] % (2 * len(cand_parents) + 2)))
-        cursor += 1
-        made = 0
+    for d in range(1, max_depth + 1):
+        if remaining == 0:
+            break
+        cap = len(prev_level) * min(max_children, vocab)
+        share = -(-remaining // (max_depth - d + 1))            # even split of what is left
+        size = min(cap, remaining if d == max_depth else max(1, share + draw() % (share + 1) - share // 2))
+        size = min(size, remaining)
+        kids = {p: set() for p in prev_level}
+        level = []
         guard = 0
-        while made < want and guard < 64 * want:
+        while len(level) < size:
             guard += 1
-            p = cand_parents[r[cursor % len(r)] % len(cand_parents)]
-            cursor += 1
-            if len(used.setdefault(p, set())) >= max_children:
+            if guard > 64 * n_draw:
+                raise ValueError("could not place the nodes")
+            p = prev_level[draw() % len(prev_level)]
+            if len(kids[p]) >= max_children:
                 continue
-            t = toks[ti % len(toks)]
+            t = toks[ti % n_draw]
             ti += 1
-            if t in used[p]:
+            if t in kids[p]:
                 continue
-            used[p].add(t)
-            parent.append(p)
+            kids[p].add(t)
             tok.append(t)
-            new_level.append(len(parent) - 1)
-            made += 1
-        if depth == len(levels):
-            levels.append(new_level)
-        if made == 0 and depth == max_depth and all(
-                len(used.get(p, ())) >= max_children for p in cand_parents):
-            raise ValueError("tree cannot hold that many nodes")
-    # rows must be ordered by (depth, creation): re-sort stably by depth
-    depth_of = [0] * len(parent)
-    for i in range(1, len(parent)):
-        depth_of[i] = depth_of[parent[i]] + 1
-    order = sorted(range(len(parent)), key=lambda i: (depth_of[i], i))
-    new_id = {old: new for new, old in enumerate(order)}
-    tok2 = [tok[o] for o in order]
-    par2 = [-1 if parent[o] < 0 else new_id[parent[o]] for o in order]
-    return (torch.tensor(tok2, dtype=torch.int32), torch.tensor(par2, dtype=torch.int32))
+            parent.append(p)
+            level.append(len(tok) - 1)
+        remaining -= size
+        prev_level = level
+    if remaining:
+        raise ValueError("tree cannot hold that many nodes")
+    return (torch.tensor(tok, dtype=torch.int32), torch.tensor(parent, dtype=torch.int32))

@@ -132,7 +132,7 @@ def test_block_from_tree(B, tiny_engine, k, layout, n_nodes):
     shape, w, eng = tiny_engine
     print(f"block_from_tree k={k} layout={layout} n={n_nodes}", flush=True)
     rows = n_nodes * (k + 1) if layout == 0 else n_nodes + k
-    blk = B.BlockBuffers(2, rows + 3, k, layout)
+    blk = B.BlockBuffers(2, min(rows + 3, 640), k, layout)
     t0, p0 = synth.make_random_tree(n_nodes, max(k, 1) if k else 6, shape.vocab, seed=30 + n_nodes)
     t1, p1 = synth.make_random_tree(max(1, n_nodes // 2), max(k, 1) if k else 6, shape.vocab, seed=31)
     blk.upload_trees([t0.tolist(), t1.tolist()], [p0.tolist(), p1.tolist()])
