@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the ESP speculate-and-verify decode step on one MI355X.
+
+One "step" = the whole hot path through the C ABI: esp_tree_forward (tree + mask rows against
+the KV cache, LM head + argmax at the tree rows), esp_verify_accept (+ KV commit), esp_mask_topk
+(LM head + softmax + Top-K' at the accepted node's mask rows) and esp_build_prune_tree.
+Workload: Llama-3-8B-shaped random bf16 decoder, KV cache of a 2048-token random prompt (prefilled
+on the GPU), 4 mask tokens, Top-K 8, tree of 64 nodes, batch 1.  All inputs are synthetic and
+resident in HBM before the timed region.
+
+Prints ONE JSON line (see the design doc for the fields).  --gpus above 1 is refused: this build is
+single-GPU by construction.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def layer_gemm_shapes(s):
+    nqkv = (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim
+    return [(nqkv, s.d_model), (s.d_model, s.n_q_heads * s.head_dim), (2 * s.d_ff, s.d_model), (s.d_model, s.d_ff)]
+
+
+def gemm_algorithmic_bytes(M, N, K):
+    """Weights once + activations in (bf16) + one fp32 result out."""
+    return 2 * N * K + 2 * M * K + 4 * M * N
+
+
+def run_config(B, decode, synth, torch, shape, weights, eng_holder, layout, n_nodes, k, K, kp, L, steps, warmup,
+               prompt, profile_every=4):
+    params = B.tree_params(n_nodes, k, K, 0, True, False, layout)
+    cap = L + (steps + warmup + 16) * (k + 1) + 1024
+    dec = decode.EspDecoder(shape, weights, params, kp, [cap], prefill_chunk=256, engine=eng_holder.get("eng"))
+    eng_holder["eng"] = dec.eng
+    eng = dec.eng
+    dec.prefill([prompt])
+    dec.step()                                   # root-only step: seeds the first 64-node tree
+    for _ in range(warmup):
+        dec.step()
+    torch.cuda.synchronize()
+    n_nodes_now = int(dec.cur.n_nodes[0])
+    rows_now = int(dec.cur.n_rows[0])
+    len0 = int(dec.kv.len[0])
+    eng.profile_read("gemm_layer")               # drop anything recorded so far
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        on = (i % profile_every) == profile_every - 1
+        eng.profile_enable(["gemm_layer"] if on else [])
+        dec.step()
+    eng.profile_enable([])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    emitted = int(dec.kv.len[0]) - len0
+    n_spans, span_ms = eng.profile_read("gemm_layer")
+    # untimed breakdown pass over every launch site
+    sites = list(B.SITES)
+    for s in sites:
+        eng.profile_read(s)
+    eng.profile_enable(sites)
+    nb = 3
+    for _ in range(nb):
+        dec.step()
+    eng.profile_enable([])
+    breakdown = {}
+    for s in sites:
+        n, ms = eng.profile_read(s)
+        breakdown[s] = {"launches_per_step": n / nb, "ms_per_step": ms / nb}
+    status = eng.device_status()
+    assert status == 0, f"device status {status}"
+    return dict(dec=dec, ms_per_step=(t1 - t0) * 1e3 / steps, emitted=emitted, n_spans=n_spans, span_ms=span_ms,
+                breakdown=breakdown, n_nodes=n_nodes_now, rows=rows_now, len_end=int(dec.kv.len[0]))
+
+
+def cpu_baseline(torch, synth, shape, weights, n_nodes, k, K, kp, L, layout):
+    """The oracle as it stands, timed on the host: one decoder layer of the workload (of 32) plus
+    the whole remainder of the step (LM head on all rows, softmax/Top-K, tree, verification),
+    extrapolated to the full depth."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import esp_oracle as O
+
+    def f64(t):
+        return t.detach().to("cpu", torch.float32).numpy().astype(np.float64)
+
+    lw = {n: f64(v) for n, v in weights["layers"][0].items()}
+    ow = {"embed": f64(weights["embed"]), "lm_head": f64(weights["lm_head"]),
+          "final_norm": f64(weights["final_norm"]), "layers": [lw]}
+    m = O.Model(1, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff, shape.vocab,
+                shape.rope_theta, shape.rms_eps, shape.qk_norm, ow)
+    one = shape.replace(n_layers=1)
+    kf, vf = synth.make_kv_fill(one, L, seed=5)
+    tok, par = synth.make_random_tree(n_nodes, k, shape.vocab, seed=7)
+    masks = f64(synth.normal_like((k, shape.d_model), 0.02, 6, 0))
+    kc, vc = [f64(kf[0])], [f64(vf[0])]
+    blk = O.make_block(tok.numpy(), par.numpy(), k, layout)
+    t0 = time.perf_counter()
+    O.tree_forward(m, blk, masks, kc, vc, L, want_logits_rows=[])
+    t_layer = time.perf_counter() - t0
+    st = O.DecodeState(kc, vc, L, tok.numpy().astype(np.int64), par.numpy().astype(np.int64), masks)
+    t0 = time.perf_counter()
+    res = O.esp_step(m, st, O.TreeParams(B=n_nodes, k=k, K=K, expand_width=0), layout, kp, "bf16")
+    t_full = time.perf_counter() - t0
+    t_step = shape.n_layers * t_layer + max(t_full - t_layer, 0.0)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": len(res.emitted) / t_step, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"oracle (numpy fp64) on 1 of {shape.n_layers} layers of the same block "
+                      f"({blk.n_rows} rows, L={L}) timed {t_layer:.1f} s, plus the rest of the step (LM head on all "
+                      f"rows, softmax/Top-K, verification, tree) {max(t_full - t_layer, 0.0):.1f} s; step time "
+                      f"extrapolated as {shape.n_layers} x layer + rest = {t_step:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layout", choices=["per_node", "root_chain"], default="per_node")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-alt", action="store_true", help="skip the second layout")
+    ap.add_argument("--kv-len", type=int, default=2048)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_17942_amd import binding as B
+    from paper_2603_17942_amd import decode, synth
+
+    B.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback of the hot path)"
+    shape = synth.SHAPES["llama3_8b"]
+    n_nodes, k, K, kp, L = 64, 4, 8, 10, args.kv_len
+    t_setup = time.perf_counter()
+    weights = synth.make_weights(shape, seed=1, device="cuda")
+    prompt = synth.make_prompt(L + 1, shape.vocab, seed=2).tolist()
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    layouts = {"per_node": B.LAYOUT_PER_NODE, "root_chain": B.LAYOUT_ROOT_CHAIN}
+    holder = {}
+    # the engine is sized for the larger layout so that both runs share the weights
+    decode.EspDecoder.default_max_rows = n_nodes * (k + 1)
+    main_r = run_config(B, decode, synth, torch, shape, weights, holder, layouts[args.layout], n_nodes, k, K, kp, L,
+                        args.steps, args.warmup, prompt)
+    alt_name = "root_chain" if args.layout == "per_node" else "per_node"
+    alt_r = None
+    if not args.no_alt:
+        alt_r = run_config(B, decode, synth, torch, shape, weights, holder, layouts[alt_name], n_nodes, k, K, kp, L,
+                           args.steps, args.warmup, prompt)
+
+    def summarise(r):
+        rows = r["rows"]
+        tokens_per_s = r["emitted"] / (r["ms_per_step"] * args.steps / 1e3)
+        shapes = layer_gemm_shapes(shape)
+        per_launch = sum(gemm_algorithmic_bytes(rows, N, Kd) for N, Kd in shapes) / len(shapes)
+        avg_ms = r["span_ms"] / max(r["n_spans"], 1)
+        achieved = per_launch / (avg_ms * 1e-3) / 1e9 if r["n_spans"] else None
+        flops = sum(2.0 * rows * N * Kd for N, Kd in shapes) / len(shapes)
+        attn = r["breakdown"]["attn"]
+        Lnow = r["len_end"]
+        attn_bytes = (Lnow + rows) * shape.n_kv_heads * shape.head_dim * 2 * 2 + \
+            2 * rows * shape.n_q_heads * shape.head_dim * 2
+        attn_ms = attn["ms_per_step"] / max(attn["launches_per_step"], 1)
+        return dict(rows=rows, n_nodes=r["n_nodes"], tokens_per_s=tokens_per_s, ms_per_step=r["ms_per_step"],
+                    tau=r["emitted"] / args.steps,
+                    roofline={"kernel": "k_gemm_bf16 (layer projections: QKV, O, gate/up, down)", "bound": "hbm",
+                              "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
+                              "bytes_per_launch": per_launch, "avg_launch_ms": avg_ms, "launches_timed": r["n_spans"],
+                              "mfma_tflops": flops / (avg_ms * 1e-3) / 1e12 if r["n_spans"] else None},
+                    roofline_attn={"kernel": "k_attn_mfma", "bound": "hbm",
+                                   "achieved": attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else None,
+                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "bytes_per_launch": attn_bytes,
+                                   "avg_launch_ms": attn_ms, "kv_len": Lnow},
+                    breakdown_ms_per_step={s: round(v["ms_per_step"], 4) for s, v in r["breakdown"].items()})
+
+    sm = summarise(main_r)
+    weight_bytes = shape.n_layers * sum(2 * N * Kd for N, Kd in layer_gemm_shapes(shape)) + \
+        2 * 2 * shape.vocab * shape.d_model
+    out = {
+        "metric": "verified tree-step latency (ms) & tokens/s at 8B shape",
+        "value": sm["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sm["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-3-8B-shaped random bf16 decoder, KV cache from a "
+                               f"{L}-token random prompt, ESP step with k=4 mask tokens, Top-K=8, tree of 64 nodes, "
+                               "batch 1", "layout": args.layout, "rows_per_step": sm["rows"],
+                   "tree_nodes": sm["n_nodes"], "kv_len": L, "tau_measured": sm["tau"],
+                   "hbm_floor_ms": weight_bytes / (HBM_PEAK_GBS * 1e9) * 1e3},
+        "roofline": sm["roofline"], "roofline_attn": sm["roofline_attn"],
+        "breakdown_ms_per_step": sm["breakdown_ms_per_step"],
+        "setup_s": round(t_setup, 1),
+    }
+    if alt_r is not None:
+        sa = summarise(alt_r)
+        out["alt_layout"] = {"layout": alt_name, "rows_per_step": sa["rows"], "tokens_per_s": sa["tokens_per_s"],
+                             "ms_per_step": sa["ms_per_step"], "roofline": sa["roofline"],
+                             "roofline_attn": sa["roofline_attn"],
+                             "breakdown_ms_per_step": sa["breakdown_ms_per_step"]}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, synth, shape, weights, n_nodes, k, K, kp, L,
+                                           layouts[args.layout])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

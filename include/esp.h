@@ -263,6 +263,23 @@ esp_status esp_softmax_topk(void *stream, const float *logits, int32_t rows, int
                             int32_t Kp, int32_t *ids, float *probs, void *scratch,
                             size_t scratch_bytes);
 
+/* Optional timing of launch sites with HIP events recorded on the ctx stream (benchmarks).
+ * esp_profile_enable: bit s of site_mask turns site s on (0 = off, the default; events are host
+ * objects, no device memory is allocated).  esp_profile_read: synchronises the stream, adds the
+ * finished spans to per-site totals and returns, then clears, the totals of `site`. */
+enum {
+  ESP_SITE_GEMM_LAYER = 0, /* QKV, O, gate/up and down projections          */
+  ESP_SITE_ATTN = 1,       /* tree attention main kernel                    */
+  ESP_SITE_ATTN_MERGE = 2,
+  ESP_SITE_LM_HEAD = 3,    /* LM-head GEMMs (tree rows and mask rows)       */
+  ESP_SITE_TOPK = 4,       /* softmax + Top-K (both passes)                 */
+  ESP_SITE_TREE = 5,       /* verify/commit, row lists, tree build          */
+  ESP_SITE_GLUE = 6,       /* embed, norms, rotary/KV append, SwiGLU, argmax */
+  ESP_SITE_COUNT = 7
+};
+esp_status esp_profile_enable(esp_ctx *ctx, uint32_t site_mask);
+esp_status esp_profile_read(esp_ctx *ctx, int32_t site, int64_t *launches, double *total_ms);
+
 #ifdef __cplusplus
 }
 #endif

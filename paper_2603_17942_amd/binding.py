@@ -60,7 +60,8 @@ EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
            "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_kv_store", "esp_kv_load",
            "esp_gemm_scratch_bytes", "esp_gemm", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
-           "esp_softmax_topk"]
+           "esp_softmax_topk", "esp_profile_enable", "esp_profile_read"]
+SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
 
 _lib = None
 
@@ -104,6 +105,8 @@ def load_library() -> C.CDLL:
     lib.esp_softmax_topk_scratch_bytes.restype = C.c_size_t
     lib.esp_softmax_topk_scratch_bytes.argtypes = [_i32, _i32, _i32]
     lib.esp_softmax_topk.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, C.c_size_t]
+    lib.esp_profile_enable.argtypes = [_vp, C.c_uint32]
+    lib.esp_profile_read.argtypes = [_vp, _i32, P(_i64), P(C.c_double)]
     for name in EXPORTS:
         getattr(lib, name)          # AttributeError here = a declared entry point is not exported
     _lib = lib
@@ -327,6 +330,18 @@ class Engine:
         b, k = blk.struct(), kv.struct()
         _check(self.lib.esp_attn_tree(self.ctx, C.byref(b), C.byref(k), layer, _ptr(q), _ptr(out)),
                "esp_attn_tree")
+
+    def profile_enable(self, sites: Sequence[str]):
+        mask = 0
+        for name in sites:
+            mask |= 1 << SITES[name]
+        _check(self.lib.esp_profile_enable(self.ctx, mask), "esp_profile_enable")
+
+    def profile_read(self, site: str):
+        """(launch spans, total ms) of a site since the last read; synchronises."""
+        n, ms = _i64(0), C.c_double(0.0)
+        _check(self.lib.esp_profile_read(self.ctx, SITES[site], C.byref(n), C.byref(ms)), "esp_profile_read")
+        return n.value, ms.value
 
     def device_status(self) -> int:
         v = _i32(0)

@@ -122,6 +122,38 @@ int nodes_bound(const esp_block* b) {
   return std::max(b->rows_per_seq - b->k_masks, 1);
 }
 
+hipEvent_t prof_event(esp_ctx* c) {
+  if (!c->prof_pool.empty()) {
+    hipEvent_t e = c->prof_pool.back();
+    c->prof_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Times everything enqueued during its lifetime when the site is enabled; otherwise free.
+struct ProfScope {
+  esp_ctx* c = nullptr;
+  hipEvent_t stop = nullptr;
+  ProfScope(esp_ctx* ctx, int site) {
+    if (!((ctx->prof_mask >> site) & 1u)) return;
+    hipEvent_t start = prof_event(ctx);
+    stop = prof_event(ctx);
+    if (!start || !stop) return;
+    c = ctx;
+    (void)hipEventRecord(start, c->stream);
+    c->prof_open.push_back({site, start, stop});
+  }
+  ~ProfScope() {
+    if (c) (void)hipEventRecord(stop, c->stream);
+  }
+};
+#define ESP_CAT2(a, b) a##b
+#define ESP_CAT(a, b) ESP_CAT2(a, b)
+#define ESP_PROF(site) ProfScope ESP_CAT(prof_scope_, __LINE__)(c, site)
+
 // sums split-K partials in split order into C
 __global__ void k_reduce_splits(const float* __restrict__ part, int splits, size_t n, float* __restrict__ out) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -207,7 +239,38 @@ esp_status esp_create(const esp_model_desc* m, const esp_weights* w, int32_t max
 
 esp_status esp_destroy(esp_ctx* ctx) {
   if (!ctx) return ESP_EINVAL;
+  for (auto& sp : ctx->prof_open) {
+    (void)hipEventDestroy(sp.start);
+    (void)hipEventDestroy(sp.stop);
+  }
+  for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
   delete ctx;
+  return ESP_OK;
+}
+
+esp_status esp_profile_enable(esp_ctx* ctx, uint32_t site_mask) {
+  if (!ctx) return ESP_EINVAL;
+  ctx->prof_mask = site_mask & ((1u << ESP_SITE_COUNT) - 1u);
+  return ESP_OK;
+}
+
+esp_status esp_profile_read(esp_ctx* ctx, int32_t site, int64_t* launches, double* total_ms) {
+  if (!ctx || !launches || !total_ms || site < 0 || site >= ESP_SITE_COUNT) return ESP_EINVAL;
+  ESP_HIP(hipStreamSynchronize(ctx->stream));
+  for (auto& sp : ctx->prof_open) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, sp.start, sp.stop) == hipSuccess) {
+      ctx->prof_ms[sp.site] += ms;
+      ctx->prof_n[sp.site] += 1;
+    }
+    ctx->prof_pool.push_back(sp.start);
+    ctx->prof_pool.push_back(sp.stop);
+  }
+  ctx->prof_open.clear();
+  *launches = ctx->prof_n[site];
+  *total_ms = ctx->prof_ms[site];
+  ctx->prof_n[site] = 0;
+  ctx->prof_ms[site] = 0.0;
   return ESP_OK;
 }
 
@@ -253,30 +316,44 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
   if (attn_partial_floats(blk->batch, blk->rows_per_seq, hq, hd, ap.nsplit) > c->attn_part_floats)
     return ESP_ECAPACITY;
 
+  { ESP_PROF(ESP_SITE_GLUE);
   ESP_HIP(launch_embed(s, dt, bd, kd, c->embed, mask_embed, c->h, d, m.vocab, c->rope_tab, hd, m.rope_theta,
                        c->status));
-  ESP_HIP(launch_residual_norm(s, dt, c->h, nullptr, 0, M, d, c->norm_attn[0], m.rms_eps, c->xn));
+  ESP_HIP(launch_residual_norm(s, dt, c->h, nullptr, 0, M, d, c->norm_attn[0], m.rms_eps, c->xn)); }
   for (int l = 0; l < m.n_layers; ++l) {
-    ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wqkv[l], c->gemm_out, M, nqkv, d, p_qkv));
-    ESP_HIP(launch_qkv_post(s, dt, bd, kd, l, c->gemm_out, p_qkv.splits, M, hq, hkv, hd, m.qk_norm, c->q_norm[l],
-                            c->k_norm[l], m.rms_eps, c->rope_tab, c->q));
-    ESP_HIP(launch_attn(s, dt, bd, kd, l, hq, hkv, hd, c->q, c->attn_part, ap, c->attn_out));
-    ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o));
-    ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_o.splits, M, d, c->norm_mlp[l], m.rms_eps, c->xn));
-    ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wgu[l], c->gemm_out, M, 2 * ff, d, p_gu));
-    ESP_HIP(launch_swiglu(s, dt, c->gemm_out, p_gu.splits, M, ff, c->act));
-    ESP_HIP(launch_gemm(s, dt, c->act, nullptr, c->wdown[l], c->gemm_out, M, d, ff, p_dn));
+    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wqkv[l], c->gemm_out, M, nqkv, d, p_qkv)); }
+    { ESP_PROF(ESP_SITE_GLUE);
+      ESP_HIP(launch_qkv_post(s, dt, bd, kd, l, c->gemm_out, p_qkv.splits, M, hq, hkv, hd, m.qk_norm, c->q_norm[l],
+                              c->k_norm[l], m.rms_eps, c->rope_tab, c->q)); }
+    { ESP_PROF(ESP_SITE_ATTN);
+      ESP_HIP(launch_attn(s, dt, bd, kd, l, hq, hkv, hd, c->q, c->attn_part, ap)); }
+    { ESP_PROF(ESP_SITE_ATTN_MERGE);
+      ESP_HIP(launch_attn_merge(s, dt, bd, kd, hq, hd, c->attn_part, ap, c->attn_out)); }
+    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+      ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o)); }
+    { ESP_PROF(ESP_SITE_GLUE);
+      ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_o.splits, M, d, c->norm_mlp[l], m.rms_eps, c->xn)); }
+    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wgu[l], c->gemm_out, M, 2 * ff, d, p_gu)); }
+    { ESP_PROF(ESP_SITE_GLUE);
+      ESP_HIP(launch_swiglu(s, dt, c->gemm_out, p_gu.splits, M, ff, c->act)); }
+    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+      ESP_HIP(launch_gemm(s, dt, c->act, nullptr, c->wdown[l], c->gemm_out, M, d, ff, p_dn)); }
     const bool last = l + 1 == m.n_layers;
-    ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_dn.splits, M, d,
-                                 last ? c->final_norm : c->norm_attn[l + 1], m.rms_eps, last ? hidden_out : c->xn));
+    { ESP_PROF(ESP_SITE_GLUE);
+      ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_dn.splits, M, d,
+                                   last ? c->final_norm : c->norm_attn[l + 1], m.rms_eps, last ? hidden_out : c->xn)); }
   }
   // LM head + argmax at the tree rows (Sec. 2 Eq. 3 needs the base model's own next token there)
   if (logits_dbg) {
     const GemmPlan p_lm = gemm_plan(dt, M, m.vocab, d);
     if (p_lm.splits != 1) return ESP_ESHAPE;
-    ESP_HIP(launch_gemm(s, dt, hidden_out, nullptr, c->lm_head, logits_dbg, M, m.vocab, d, p_lm));
+    { ESP_PROF(ESP_SITE_LM_HEAD);
+      ESP_HIP(launch_gemm(s, dt, hidden_out, nullptr, c->lm_head, logits_dbg, M, m.vocab, d, p_lm)); }
     if (node_argmax) {
       const int nb = nodes_bound(blk);
+      ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b));
       ESP_HIP(launch_argmax(s, logits_dbg, (size_t)m.vocab, c->idx_a, blk->batch * nb, m.vocab, node_argmax,
                             c->idx_b));
@@ -287,9 +364,12 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     if ((size_t)Mn > c->logits_rows) return ESP_ECAPACITY;
     const GemmPlan p_lm = gemm_plan(dt, Mn, m.vocab, d);
     if (p_lm.splits != 1) return ESP_ESHAPE;
-    ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b));
-    ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm));
-    ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b));
+    { ESP_PROF(ESP_SITE_GLUE);
+      ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b)); }
+    { ESP_PROF(ESP_SITE_LM_HEAD);
+      ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm)); }
+    { ESP_PROF(ESP_SITE_GLUE);
+      ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b)); }
   }
   return ESP_OK;
 }
@@ -302,6 +382,7 @@ esp_status esp_verify_accept(esp_ctx* c, const esp_block* blk, const int32_t* no
   st = check_kv(c, kv, blk);
   if (st != ESP_OK) return st;
   if (!node_argmax || !n_emit || !emit_tok || !accepted_row || !star_row) return ESP_EINVAL;
+  ESP_PROF(ESP_SITE_TREE);
   ESP_HIP(launch_verify_accept(c->stream, c->m.dtype, to_dev(blk), to_dev(kv), node_argmax, c->m.n_layers,
                                c->m.n_kv_heads, c->m.head_dim, n_emit, emit_tok, accepted_row, star_row,
                                c->status));
@@ -320,12 +401,15 @@ esp_status esp_mask_topk(esp_ctx* c, const esp_block* blk, const int32_t* star_r
   const int rows = blk->batch * blk->k_masks;
   hipStream_t s = c->stream;
   BlockDev bd = to_dev(blk);
-  ESP_HIP(launch_mask_rows(s, bd, star_row, n_emit, c->idx_a, n_lists));
+  { ESP_PROF(ESP_SITE_TREE);
+    ESP_HIP(launch_mask_rows(s, bd, star_row, n_emit, c->idx_a, n_lists)); }
   const GemmPlan p_lm = gemm_plan(m.dtype, rows, m.vocab, m.d_model);
   if (p_lm.splits != 1) return ESP_ESHAPE;
   float* lg = logits_out ? logits_out : c->logits;
-  ESP_HIP(launch_gemm(s, m.dtype, hidden, c->idx_a, c->lm_head, lg, rows, m.vocab, m.d_model, p_lm));
-  ESP_HIP(launch_softmax_topk(s, lg, rows, m.vocab, Kp, topk_id, topk_p, c->topk_scratch));
+  { ESP_PROF(ESP_SITE_LM_HEAD);
+    ESP_HIP(launch_gemm(s, m.dtype, hidden, c->idx_a, c->lm_head, lg, rows, m.vocab, m.d_model, p_lm)); }
+  { ESP_PROF(ESP_SITE_TOPK);
+    ESP_HIP(launch_softmax_topk(s, lg, rows, m.vocab, Kp, topk_id, topk_p, c->topk_scratch)); }
   return ESP_OK;
 }
 
@@ -364,6 +448,7 @@ esp_status esp_build_prune_tree(esp_ctx* c, const esp_tree_params* p, const int3
     }
     if (total > 4096) return ESP_ECAPACITY;
   }
+  ESP_PROF(ESP_SITE_TREE);
   ESP_HIP(launch_build_tree(c->stream, *p, next->batch, topk_id, topk_p, Kp, n_lists, n_emit, emit_tok,
                             next->rows_per_seq, next->anc_words, next->n_rows, next->n_nodes, next->tok,
                             next->parent, next->depth, next->mask_j, next->attach, next->anc, c->status));
@@ -458,8 +543,12 @@ esp_status esp_attn_tree(esp_ctx* c, const esp_block* blk, const esp_kv* kv, int
   const AttnPlan ap = attn_plan(blk->batch, blk->rows_per_seq, m.n_q_heads, m.n_kv_heads, kv->len_bound);
   if (attn_partial_floats(blk->batch, blk->rows_per_seq, m.n_q_heads, m.head_dim, ap.nsplit) > c->attn_part_floats)
     return ESP_ECAPACITY;
-  ESP_HIP(launch_attn(c->stream, m.dtype, to_dev(blk), to_dev(kv), layer, m.n_q_heads, m.n_kv_heads, m.head_dim, q,
-                      c->attn_part, ap, out));
+  { ESP_PROF(ESP_SITE_ATTN);
+    ESP_HIP(launch_attn(c->stream, m.dtype, to_dev(blk), to_dev(kv), layer, m.n_q_heads, m.n_kv_heads, m.head_dim, q,
+                        c->attn_part, ap)); }
+  { ESP_PROF(ESP_SITE_ATTN_MERGE);
+    ESP_HIP(launch_attn_merge(c->stream, m.dtype, to_dev(blk), to_dev(kv), m.n_q_heads, m.head_dim, c->attn_part, ap,
+                              out)); }
   return ESP_OK;
 }
 

@@ -376,7 +376,7 @@ size_t attn_partial_floats(int batch, int rows_per_seq, int hq, int hd, int nspl
 }
 
 hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer, int hq, int hkv,
-                       int hd, const void* q, float* partials, const AttnPlan& p, void* out) {
+                       int hd, const void* q, float* partials, const AttnPlan& p) {
   const int M = b.batch * b.rows_per_seq;
   float* part_o = partials;
   float* part_ml = partials + (size_t)M * hq * p.nsplit * hd;
@@ -435,8 +435,14 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
     else
       return hipErrorInvalidValue;
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int hq, int hd,
+                             const float* partials, const AttnPlan& p, void* out) {
+  const int M = b.batch * b.rows_per_seq;
+  const float* part_o = partials;
+  const float* part_ml = partials + (size_t)M * hq * p.nsplit * hd;
   if (dtype == ESP_F32)
     hipLaunchKernelGGL(k_attn_merge<float>, dim3(M * hq), dim3(hd), 0, st, b, kv, hq, hd, part_o, part_ml, p.nsplit,
                        (float*)out);

@@ -97,7 +97,9 @@ struct AttnPlan { int nsplit; int tiles_per_split; };
 AttnPlan attn_plan(int batch, int rows_per_seq, int hq, int hkv, int len_bound);
 size_t attn_partial_floats(int batch, int rows_per_seq, int hq, int hd, int nsplit);
 hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer, int hq,
-                       int hkv, int hd, const void* q, float* partials, const AttnPlan& p, void* out);
+                       int hkv, int hd, const void* q, float* partials, const AttnPlan& p);
+hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int hq, int hd,
+                             const float* partials, const AttnPlan& p, void* out);
 
 // ---- softmax + top-k (esp_topk.hip) -----------------------------------------------------------
 size_t softmax_topk_scratch_floats(int rows, int vocab, int kp);
@@ -145,4 +147,11 @@ struct esp_ctx {
   int32_t* idx_b;    // [Mmax]
   int32_t* status;   // device status word
   size_t gemm_out_floats, attn_part_floats, logits_rows;
+  // optional launch-site timing with HIP events (esp_profile_enable / esp_profile_read)
+  struct ProfSpan { int site; hipEvent_t start, stop; };
+  uint32_t prof_mask = 0;
+  std::vector<ProfSpan> prof_open;
+  std::vector<hipEvent_t> prof_pool;
+  double prof_ms[ESP_SITE_COUNT] = {};
+  int64_t prof_n[ESP_SITE_COUNT] = {};
 };

@@ -18,9 +18,11 @@ def rows_for(n_nodes: int, k: int, layout: int) -> int:
 
 
 class EspDecoder:
+    default_max_rows = 0     # lower bound of the row capacity new engines are created with
+
     def __init__(self, shape: synth.ModelShape, weights: dict, params: B.TreeParams, kp: int,
                  seq_caps: Sequence[int], prefill_chunk: int = 256, max_nodes: Optional[int] = None,
-                 ema_lambda: float = 0.0, device="cuda"):
+                 ema_lambda: float = 0.0, device="cuda", engine: Optional[B.Engine] = None):
         self.shape, self.params, self.kp, self.device = shape, params, kp, device
         self.k, self.layout = params.k, params.layout
         self.batch = len(seq_caps)
@@ -30,9 +32,11 @@ class EspDecoder:
             nodes = 1 + sum(params.static_widths[i] for i in range(params.k))
         self.rows_per_seq = rows_for(nodes, self.k, self.layout)
         self.prefill_chunk = prefill_chunk
-        max_rows = max(self.rows_per_seq, prefill_chunk)
+        max_rows = max(self.rows_per_seq, prefill_chunk, EspDecoder.default_max_rows)
         self.kv = B.KvCache(shape, seq_caps, device)
-        self.eng = B.Engine(shape, weights, self.batch, max_rows, max(self.kv.caps), device)
+        # an engine (weights + workspace) can be shared by decoders that fit its limits
+        self.eng = engine if engine is not None else \
+            B.Engine(shape, weights, self.batch, max_rows, max(self.kv.caps), device)
         dt = self.eng.dt
         M = self.batch * self.rows_per_seq
         i32 = dict(dtype=torch.int32, device=device)
@@ -55,7 +59,6 @@ class EspDecoder:
     def prefill(self, prompts: Sequence[Sequence[int]]):
         assert len(prompts) == self.batch
         lens = [len(p) - 1 for p in prompts]
-        assert len(set(lens)) == 1 or self.batch == 1 or True
         self.kv.set_len([0] * self.batch)
         done = [0] * self.batch
         chunk = self.prefill_chunk
