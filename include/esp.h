@@ -87,6 +87,8 @@ typedef struct {
 typedef struct {
   const void *embed;             /* [vocab, d_model]                                   */
   const void *lm_head;           /* [vocab, d_model] (untied)                          */
+                                 /* bf16 models: every matrix below and lm_head in the */
+                                 /* layout of esp_pack_weight; embed stays row-major   */
   const void *final_norm;        /* [d_model]                                          */
   const void *const *wqkv;       /* [(n_q + 2 n_kv) * head_dim, d_model]: q, k, v rows */
   const void *const *wo;         /* [d_model, n_q * head_dim]                          */
@@ -242,12 +244,20 @@ esp_status esp_kv_store(esp_ctx *ctx, const esp_kv *kv, int32_t layer, int32_t s
 esp_status esp_kv_load(esp_ctx *ctx, const esp_kv *kv, int32_t layer, int32_t seq_base,
                        int32_t first_slot, int32_t n_slots, void *k_rows, void *v_rows);
 
+/* Rewrites a row-major bf16 matrix W[N,K] (device) into the streaming layout the bf16 GEMMs read:
+ * tiles of 32 output rows x 64 inputs, each 4 KB contiguous in MFMA operand order, tiles ordered
+ * [K/64][N/32].  dst: device, N*K bf16, must not alias src.  Needs N % 32 == 0, K % 64 == 0.
+ * Every bf16 matrix handed to esp_create (wqkv, wo, w_gate_up, w_down, lm_head) must be in this
+ * layout; embed and the norm gains stay plain.  fp32 models use plain row-major matrices. */
+esp_status esp_pack_weight(void *stream, const void *src, void *dst, int32_t N, int32_t K);
+
 /* C[M,N] (fp32, device) = A[M,K] * W[N,K]^T, A and W in `dtype` (device), on `stream`.
- * bf16 needs N % 32 == 0 and K % 64 == 0.  `partials` is device scratch of
- * esp_gemm_scratch_bytes(M,N,K) bytes (split-K partial sums; reduced in a fixed order). */
+ * bf16 needs N % 32 == 0 and K % 64 == 0; w_packed != 0: W is in the streaming layout.
+ * `partials` is device scratch of esp_gemm_scratch_bytes(M,N,K) bytes (split-K partial sums;
+ * reduced in a fixed order). */
 size_t esp_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
-esp_status esp_gemm(void *stream, int32_t dtype, const void *A, const void *W, float *C, int32_t M,
-                    int32_t N, int32_t K, void *partials, size_t partial_bytes);
+esp_status esp_gemm(void *stream, int32_t dtype, const void *A, const void *W, int32_t w_packed,
+                    float *C, int32_t M, int32_t N, int32_t K, void *partials, size_t partial_bytes);
 
 /* Tree-masked grouped-query attention of one layer (the kernel esp_tree_forward uses):
  * q device [batch*rows_per_seq, n_q_heads, head_dim] model dtype, already rotated; K/V of the

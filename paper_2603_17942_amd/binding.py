@@ -60,7 +60,7 @@ EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
            "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_kv_store", "esp_kv_load",
            "esp_gemm_scratch_bytes", "esp_gemm", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
-           "esp_softmax_topk", "esp_profile_enable", "esp_profile_read"]
+           "esp_softmax_topk", "esp_profile_enable", "esp_profile_read", "esp_pack_weight"]
 SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
 
 _lib = None
@@ -100,7 +100,8 @@ def load_library() -> C.CDLL:
     lib.esp_kv_load.argtypes = [_vp, P(Kv), _i32, _i32, _i32, _i32, _vp, _vp]
     lib.esp_gemm_scratch_bytes.restype = C.c_size_t
     lib.esp_gemm_scratch_bytes.argtypes = [_i32, _i32, _i32]
-    lib.esp_gemm.argtypes = [_vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t]
+    lib.esp_gemm.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _vp, C.c_size_t]
+    lib.esp_pack_weight.argtypes = [_vp, _vp, _vp, _i32, _i32]
     lib.esp_attn_tree.argtypes = [_vp, P(Block), P(Kv), _i32, _vp, _vp]
     lib.esp_softmax_topk_scratch_bytes.restype = C.c_size_t
     lib.esp_softmax_topk_scratch_bytes.argtypes = [_i32, _i32, _i32]
@@ -229,20 +230,28 @@ class Engine:
             self._keep.append(t)
             return t
 
+        def mat(t):
+            """Matrix for the GEMMs: bf16 models hand over the streaming layout."""
+            t = t.to(device=device, dtype=self.dt).contiguous()
+            if self.dt == torch.bfloat16:
+                t = pack_weight(t)
+            self._keep.append(t)
+            return t
+
         arrs = {n: (_vp * L)() for n in ("wqkv", "wo", "w_gate_up", "w_down", "norm_attn", "norm_mlp",
                                           "q_norm", "k_norm")}
         for l in range(L):
             w = lw[l]
-            arrs["wqkv"][l] = dev(torch.cat([w["wq"], w["wk"], w["wv"]], 0)).data_ptr()
-            arrs["wo"][l] = dev(w["wo"]).data_ptr()
-            arrs["w_gate_up"][l] = dev(torch.cat([w["w_gate"], w["w_up"]], 0)).data_ptr()
-            arrs["w_down"][l] = dev(w["w_down"]).data_ptr()
+            arrs["wqkv"][l] = mat(torch.cat([w["wq"], w["wk"], w["wv"]], 0)).data_ptr()
+            arrs["wo"][l] = mat(w["wo"]).data_ptr()
+            arrs["w_gate_up"][l] = mat(torch.cat([w["w_gate"], w["w_up"]], 0)).data_ptr()
+            arrs["w_down"][l] = mat(w["w_down"]).data_ptr()
             arrs["norm_attn"][l] = dev(w["norm_attn"]).data_ptr()
             arrs["norm_mlp"][l] = dev(w["norm_mlp"]).data_ptr()
             arrs["q_norm"][l] = dev(w["q_norm"]).data_ptr()
             arrs["k_norm"][l] = dev(w["k_norm"]).data_ptr()
         self.embed = dev(weights["embed"])
-        self.lm_head = dev(weights["lm_head"])
+        self.lm_head = mat(weights["lm_head"])
         self.final_norm = dev(weights["final_norm"])
         self._arrs = arrs
         pp = lambda n: C.cast(arrs[n], C.POINTER(_vp))
@@ -359,8 +368,17 @@ def tree_params(B: int, k: int, K: int, expand_width: int = 1, prune_parent: boo
     return TreeParams(B, k, K, expand_width, int(prune_parent), int(prune_last), layout, sw)
 
 
-def gemm(A: torch.Tensor, W: torch.Tensor) -> torch.Tensor:
-    """out[M,N] fp32 = A[M,K] @ W[N,K]^T through esp_gemm."""
+def pack_weight(w: torch.Tensor) -> torch.Tensor:
+    """Row-major bf16 [N,K] -> the library's streaming layout (esp_pack_weight), same shape tag."""
+    lib = load_library()
+    assert w.dtype == torch.bfloat16 and w.dim() == 2 and w.is_contiguous()
+    out = torch.empty_like(w)
+    _check(lib.esp_pack_weight(_stream_ptr(), _ptr(w), _ptr(out), w.shape[0], w.shape[1]), "esp_pack_weight")
+    return out
+
+
+def gemm(A: torch.Tensor, W: torch.Tensor, packed: bool = False) -> torch.Tensor:
+    """out[M,N] fp32 = A[M,K] @ W[N,K]^T through esp_gemm (W row-major, or packed by pack_weight)."""
     lib = load_library()
     M, K = A.shape
     N = W.shape[0]
@@ -368,7 +386,8 @@ def gemm(A: torch.Tensor, W: torch.Tensor) -> torch.Tensor:
     out = torch.empty((M, N), dtype=torch.float32, device=A.device)
     nb = lib.esp_gemm_scratch_bytes(M, N, K)
     scratch = torch.empty(max(nb, 256), dtype=torch.uint8, device=A.device)
-    _check(lib.esp_gemm(_stream_ptr(), code, _ptr(A), _ptr(W), _ptr(out), M, N, K, _ptr(scratch), nb), "esp_gemm")
+    _check(lib.esp_gemm(_stream_ptr(), code, _ptr(A), _ptr(W), int(packed), _ptr(out), M, N, K, _ptr(scratch),
+                        nb), "esp_gemm")
     return out
 
 

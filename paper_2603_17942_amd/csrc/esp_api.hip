@@ -22,6 +22,7 @@ esp_status check_model(const esp_model_desc* m) {
     return ESP_EINVAL;
   if (m->n_q_heads % m->n_kv_heads) return ESP_ESHAPE;
   if (m->head_dim != 64 && m->head_dim != 128) return ESP_ESHAPE;
+  if (m->d_model % 4 || m->d_ff % 4) return ESP_ESHAPE;   // float4 paths of the glue kernels
   if (m->dtype == ESP_BF16) {
     // MFMA GEMM: K multiple of 64, N multiple of 32
     if (m->d_model % 64 || m->d_ff % 64 || (m->n_q_heads * m->head_dim) % 64 || m->vocab % 32) return ESP_ESHAPE;
@@ -304,6 +305,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
   hipStream_t s = c->stream;
   BlockDev bd = to_dev(blk);
   KvDev kd = to_dev(kv);
+  const bool pk = dt == ESP_BF16;   // bf16 matrices arrive in the streaming layout
 
   const GemmPlan p_qkv = gemm_plan(dt, M, nqkv, d);
   const GemmPlan p_o = gemm_plan(dt, M, d, hq * hd);
@@ -322,7 +324,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
   ESP_HIP(launch_residual_norm(s, dt, c->h, nullptr, 0, M, d, c->norm_attn[0], m.rms_eps, c->xn)); }
   for (int l = 0; l < m.n_layers; ++l) {
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
-      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wqkv[l], c->gemm_out, M, nqkv, d, p_qkv)); }
+      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wqkv[l], c->gemm_out, M, nqkv, d, p_qkv, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_qkv_post(s, dt, bd, kd, l, c->gemm_out, p_qkv.splits, M, hq, hkv, hd, m.qk_norm, c->q_norm[l],
                               c->k_norm[l], m.rms_eps, c->rope_tab, c->q)); }
@@ -331,15 +333,15 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     { ESP_PROF(ESP_SITE_ATTN_MERGE);
       ESP_HIP(launch_attn_merge(s, dt, bd, kd, hq, hd, c->attn_part, ap, c->attn_out)); }
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
-      ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o)); }
+      ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_o.splits, M, d, c->norm_mlp[l], m.rms_eps, c->xn)); }
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
-      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wgu[l], c->gemm_out, M, 2 * ff, d, p_gu)); }
+      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wgu[l], c->gemm_out, M, 2 * ff, d, p_gu, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_swiglu(s, dt, c->gemm_out, p_gu.splits, M, ff, c->act)); }
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
-      ESP_HIP(launch_gemm(s, dt, c->act, nullptr, c->wdown[l], c->gemm_out, M, d, ff, p_dn)); }
+      ESP_HIP(launch_gemm(s, dt, c->act, nullptr, c->wdown[l], c->gemm_out, M, d, ff, p_dn, pk)); }
     const bool last = l + 1 == m.n_layers;
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_dn.splits, M, d,
@@ -350,7 +352,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     const GemmPlan p_lm = gemm_plan(dt, M, m.vocab, d);
     if (p_lm.splits != 1) return ESP_ESHAPE;
     { ESP_PROF(ESP_SITE_LM_HEAD);
-      ESP_HIP(launch_gemm(s, dt, hidden_out, nullptr, c->lm_head, logits_dbg, M, m.vocab, d, p_lm)); }
+      ESP_HIP(launch_gemm(s, dt, hidden_out, nullptr, c->lm_head, logits_dbg, M, m.vocab, d, p_lm, pk)); }
     if (node_argmax) {
       const int nb = nodes_bound(blk);
       ESP_PROF(ESP_SITE_GLUE);
@@ -367,7 +369,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b)); }
     { ESP_PROF(ESP_SITE_LM_HEAD);
-      ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm)); }
+      ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b)); }
   }
@@ -407,7 +409,7 @@ esp_status esp_mask_topk(esp_ctx* c, const esp_block* blk, const int32_t* star_r
   if (p_lm.splits != 1) return ESP_ESHAPE;
   float* lg = logits_out ? logits_out : c->logits;
   { ESP_PROF(ESP_SITE_LM_HEAD);
-    ESP_HIP(launch_gemm(s, m.dtype, hidden, c->idx_a, c->lm_head, lg, rows, m.vocab, m.d_model, p_lm)); }
+    ESP_HIP(launch_gemm(s, m.dtype, hidden, c->idx_a, c->lm_head, lg, rows, m.vocab, m.d_model, p_lm, m.dtype == ESP_BF16)); }
   { ESP_PROF(ESP_SITE_TOPK);
     ESP_HIP(launch_softmax_topk(s, lg, rows, m.vocab, Kp, topk_id, topk_p, c->topk_scratch)); }
   return ESP_OK;
@@ -511,19 +513,27 @@ size_t esp_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   return gemm_out_elems(p, M, N) * 4 + 256;
 }
 
-esp_status esp_gemm(void* stream, int32_t dtype, const void* A, const void* W, float* C, int32_t M, int32_t N,
-                    int32_t K, void* partials, size_t partial_bytes) {
+esp_status esp_pack_weight(void* stream, const void* src, void* dst, int32_t N, int32_t K) {
+  if (!src || !dst || src == dst) return ESP_EINVAL;
+  if (N < 32 || K < 64 || N % 32 || K % 64) return ESP_ESHAPE;
+  ESP_HIP(launch_pack_weight((hipStream_t)stream, src, dst, N, K));
+  return ESP_OK;
+}
+
+esp_status esp_gemm(void* stream, int32_t dtype, const void* A, const void* W, int32_t w_packed, float* C, int32_t M,
+                    int32_t N, int32_t K, void* partials, size_t partial_bytes) {
   if (!A || !W || !C || M < 1 || N < 1 || K < 1) return ESP_EINVAL;
   if (dtype != ESP_F32 && dtype != ESP_BF16) return ESP_EDTYPE;
   if (dtype == ESP_BF16 && (N % 32 || K % 64)) return ESP_ESHAPE;
+  if (w_packed && dtype != ESP_BF16) return ESP_EDTYPE;
   GemmPlan p = gemm_plan(dtype, M, N, K);
   hipStream_t s = (hipStream_t)stream;
   if (p.splits == 1) {
-    ESP_HIP(launch_gemm(s, dtype, A, nullptr, W, C, M, N, K, p));
+    ESP_HIP(launch_gemm(s, dtype, A, nullptr, W, C, M, N, K, p, w_packed != 0));
     return ESP_OK;
   }
   if (!partials || partial_bytes < gemm_out_elems(p, M, N) * 4) return ESP_ECAPACITY;
-  ESP_HIP(launch_gemm(s, dtype, A, nullptr, W, (float*)partials, M, N, K, p));
+  ESP_HIP(launch_gemm(s, dtype, A, nullptr, W, (float*)partials, M, N, K, p, w_packed != 0));
   size_t n = (size_t)M * N;
   hipLaunchKernelGGL(k_reduce_splits, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)partials,
                      p.splits, n, C);

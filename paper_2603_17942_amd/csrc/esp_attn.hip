@@ -146,7 +146,7 @@ __device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char
 }
 
 template <int W>
-__global__ __launch_bounds__(64 * W) void k_attn_mfma(BlockDev b, KvDev kv, int layer, int hq, int hkv,
+__global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, int layer, int hq, int hkv,
                                                       const bf16_t* __restrict__ q, float* __restrict__ part_o,
                                                       float* __restrict__ part_ml, int nsplit, int tps) {
   constexpr int HD = 128;
@@ -362,7 +362,7 @@ AttnPlan attn_plan(int batch, int rows_per_seq, int hq, int hkv, int len_bound) 
   int qtiles = (rows_per_seq * G + 127) / 128;
   int base = qtiles * hkv * batch;
   int want = (768 + base - 1) / base;
-  int max_by_len = (nt + 3) / 4;      // at least 4 key tiles per split
+  int max_by_len = (nt + 1) / 2;      // at least 2 key tiles per split
   int ns = want < max_by_len ? want : max_by_len;
   if (ns < 1) ns = 1;
   if (ns > 64) ns = 64;
@@ -384,9 +384,9 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
     const int G = hq / hkv;
     const int cols = b.rows_per_seq * G;
     const int wave_tiles = (cols + 31) / 32;
-    // waves per workgroup: the count in 1..4 that pads the column range least (ties: larger)
+    // waves per workgroup: the count in 2..4 that pads the column range least (ties: larger)
     int W = 4, best_pad = 1 << 30;
-    for (int w = 4; w >= 1; --w) {
+    for (int w = 4; w >= 2; --w) {
       int pad = ((wave_tiles + w - 1) / w) * w - wave_tiles;
       if (pad < best_pad) { best_pad = pad; W = w; }
     }
@@ -395,8 +395,7 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
     // more than 64 KB of dynamic LDS must be granted per kernel once
     static bool lds_granted = false;
     if (!lds_granted) {
-      hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<1>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipError_t e1 = hipSuccess;
       hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<2>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<3>),
@@ -415,7 +414,6 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
                        part_o, part_ml, p.nsplit, p.tiles_per_split);                                     \
     break;
     switch (W) {
-      ESP_ATTN_CASE(1)
       ESP_ATTN_CASE(2)
       ESP_ATTN_CASE(3)
       ESP_ATTN_CASE(4)

@@ -79,29 +79,59 @@ hipError_t launch_embed(hipStream_t st, int dtype, const BlockDev& b, const KvDe
 }
 
 // ---- residual add of split-K partials + RMSNorm ------------------------------------------------
+// One workgroup of 1024 threads per row; a thread owns float4 columns, so all split loads of a
+// column are independent and in flight together.  d must be a multiple of 4.
+template <typename T> struct Pack4;
+template <> struct Pack4<float> {
+  static __device__ __forceinline__ void store(float* p, f32x4_t v) { *reinterpret_cast<f32x4_t*>(p) = v; }
+  static __device__ __forceinline__ f32x4_t load(const float* p) { return *reinterpret_cast<const f32x4_t*>(p); }
+};
+template <> struct Pack4<bf16_t> {
+  static __device__ __forceinline__ void store(bf16_t* p, f32x4_t v) {
+    bf16x4_t o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+    *reinterpret_cast<bf16x4_t*>(p) = o;
+  }
+  static __device__ __forceinline__ f32x4_t load(const bf16_t* p) {
+    bf16x4_t i = *reinterpret_cast<const bf16x4_t*>(p);
+    f32x4_t o = {(float)i[0], (float)i[1], (float)i[2], (float)i[3]};
+    return o;
+  }
+};
+
 template <typename T>
-__global__ __launch_bounds__(256) void k_residual_norm(float* __restrict__ h, const float* __restrict__ part,
-                                                       int splits, size_t split_stride, int d,
-                                                       const T* __restrict__ gain, float eps,
-                                                       T* __restrict__ xn) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(1024) void k_residual_norm(float* __restrict__ h, const float* __restrict__ part,
+                                                        int splits, size_t split_stride, int d,
+                                                        const T* __restrict__ gain, float eps,
+                                                        T* __restrict__ xn) {
+  __shared__ float red[16];
   const size_t row = blockIdx.x;
   float* hr = h + row * d;
+  const int d4 = d >> 2;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = hr[i];
-    for (int s = 0; s < splits; ++s) v += part[(size_t)s * split_stride + row * d + i];
-    hr[i] = v;
-    ss += v * v;
+  for (int i = threadIdx.x; i < d4; i += 1024) {
+    f32x4_t v = *reinterpret_cast<const f32x4_t*>(hr + 4 * i);
+    for (int s = 0; s < splits; ++s)
+      v += *reinterpret_cast<const f32x4_t*>(part + (size_t)s * split_stride + row * d + 4 * i);
+    *reinterpret_cast<f32x4_t*>(hr + 4 * i) = v;
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
-  float tot = block_sum_256(ss, red);
-  float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) xn[row * d + i] = from_f32<T>(hr[i] * inv * to_f32(gain[i]));
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) tot += red[w];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d4; i += 1024) {
+    f32x4_t v = *reinterpret_cast<const f32x4_t*>(hr + 4 * i);   // written by this thread above
+    f32x4_t g = Pack4<T>::load(gain + 4 * i);
+    Pack4<T>::store(xn + row * d + 4 * i, v * inv * g);
+  }
 }
 
 hipError_t launch_residual_norm(hipStream_t st, int dtype, float* h, const float* part, int splits, int M,
                                 int d, const void* gain, float eps, void* xn_out) {
-  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_residual_norm<T>, dim3(M), dim3(256), 0, st, h, part, splits,
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_residual_norm<T>, dim3(M), dim3(1024), 0, st, h, part, splits,
                                          (size_t)M * d, d, (const T*)gain, eps, (T*)xn_out));
   return hipGetLastError();
 }
@@ -181,27 +211,31 @@ hipError_t launch_qkv_post(hipStream_t st, int dtype, const BlockDev& b, const K
 }
 
 // ---- SwiGLU over the fused gate/up GEMM output ---------------------------------------------------
+// one thread per 4 consecutive features (d_ff multiple of 4)
 template <typename T>
 __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, int splits, size_t split_stride,
-                                                int dff, T* __restrict__ act, size_t total) {
+                                                int dff, T* __restrict__ act, size_t total4) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  size_t row = i / dff;
-  int j = (int)(i % dff);
-  float g = 0.f, u = 0.f;
+  if (i >= total4) return;
+  const int per_row = dff >> 2;
+  size_t row = i / per_row;
+  int j = (int)(i % per_row) * 4;
+  f32x4_t g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < splits; ++s) {
     const float* p = part + (size_t)s * split_stride + row * 2 * dff;
-    g += p[j];
-    u += p[dff + j];
+    g += *reinterpret_cast<const f32x4_t*>(p + j);
+    u += *reinterpret_cast<const f32x4_t*>(p + dff + j);
   }
-  float sg = g / (1.0f + expf(-g));
-  act[i] = from_f32<T>(sg * u);
+  f32x4_t o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+  Pack4<T>::store(act + row * dff + j, o);
 }
 
 hipError_t launch_swiglu(hipStream_t st, int dtype, const float* part, int splits, int M, int dff, void* act) {
-  size_t total = (size_t)M * dff;
-  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                                         part, splits, (size_t)M * 2 * dff, dff, (T*)act, total));
+  size_t total4 = (size_t)M * (dff >> 2);
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, st,
+                                         part, splits, (size_t)M * 2 * dff, dff, (T*)act, total4));
   return hipGetLastError();
 }
 

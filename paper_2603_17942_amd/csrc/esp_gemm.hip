@@ -1,26 +1,33 @@
 // Dense projections of the decoder: out[s][M][N] (fp32 partial sums over split s) = A[M,K] * W[N,K]^T.
 //
 // bf16 path (the 8B-class workloads): M is the number of block rows (tens to hundreds) while W is
-// hundreds of MB per layer, so the kernel is a weight streamer.  Each wave owns NB blocks of 32
-// weight rows and reads them straight from HBM into the MFMA B-operand registers, 64 contiguous
-// bytes per lane and K-chunk, through a register ring that keeps several chunks in flight; no LDS
-// hop for the weights.  The activations (L2 resident) are staged once per workgroup in LDS and
-// shared by its four waves.  v_mfma_f32_32x32x16_bf16, fp32 accumulation.
-// The order of k inside one MFMA is permuted identically for both operands (a lane takes its 8
-// values of step s from offset 32*(lane/32) + 8*s of the chunk), which leaves the dot product
-// unchanged and makes each lane's weight bytes contiguous.
-// Split-K (grid z) depends on (N, K) only, and partial sums are reduced by the consumer in split
-// order, so a row's result does not depend on how many other rows the block holds.
+// hundreds of MB per layer, so the kernel is a weight streamer.
+//  * Weights live in HBM in a streaming layout (k_pack_weight): the 32-row x 64-k tile of a wave and
+//    K-chunk is stored as [step][lane][8 values] = 4 KB contiguous in MFMA B-operand order, so every
+//    wave-wide load covers 1 KB of consecutive addresses and the data goes HBM -> VGPR -> MFMA with no
+//    LDS hop.  Tiles are ordered chunk-major ([chunk][row block]): at any moment the waves of the
+//    whole grid, which advance through the chunks together, read one contiguous window of HBM.  Inside a chunk the k index is permuted identically for both operands (lane group g,
+//    step s holds k = 32 g + 8 s + 0..7), which leaves the dot product unchanged.
+//  * A register ring keeps D chunks of weights in flight per wave.  The activations of a chunk (L2
+//    resident, shared by the four waves through LDS) ride in a ring of the same depth and are issued
+//    together with the weights of the same chunk: loads retire in order, so waiting for the
+//    activations of chunk c+1 leaves the D-2 younger chunks of the weight stream in flight.
+//  * v_mfma_f32_32x32x16_bf16, fp32 accumulation; LDS fragment reads are double-buffered one MFMA
+//    step ahead.
+//  * Split-K (grid z) depends on (N, K) only and partial sums are reduced by the consumer in split
+//    order, so a row's result does not depend on how many other rows the block holds.
 //
-// fp32 path (tiny configuration): plain LDS-tiled FMA kernel with bounds checks.
+// fp32 path (tiny configuration): plain LDS-tiled FMA kernel with bounds checks, row-major weights.
 #include "esp_internal.h"
 
 namespace {
 
-constexpr int KC = 64;          // k per chunk
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int KC = 64;            // k per chunk
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
-template <int MT, int NB, int D>
+template <int MT, int NB, int D, bool TILED>   // D even
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
                                                    int N, int K, int splits, int m_tiles, int n_tiles) {
@@ -45,13 +52,21 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   const int c_begin = z * cps;
   const int c_end = min(chunks, c_begin + cps);
 
-  // weight row pointers (clamped: out-of-range column blocks are computed but never stored)
-  const uint4* wp[NB];
+  // weight pointers (clamped: out-of-range column blocks are computed but never stored)
+  const u32x4_t* wp[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    int n = min(n0 + nb * 32 + lr, N - 1);
-    wp[nb] = reinterpret_cast<const uint4*>(W + (size_t)n * K + 32 * lg);
+    if (TILED) {
+      int blk = min((n0 + nb * 32) >> 5, (N >> 5) - 1);
+      wp[nb] = reinterpret_cast<const u32x4_t*>(W) + (size_t)blk * 256 + lane;
+    } else {
+      int n = min(n0 + nb * 32 + lr, N - 1);
+      wp[nb] = reinterpret_cast<const u32x4_t*>(W + (size_t)n * K + 32 * lg);
+    }
   }
+  const size_t W_CHUNK = TILED ? (size_t)(N >> 5) * 256 : KC * 2 / 16;   // u32x4_t between chunks of a lane's stream
+  constexpr int W_STEP = TILED ? 64 : 1;               // u32x4_t between the steps of a chunk
+
   // activation staging: thread handles MT pieces of 16 B; piece p -> row p/8, 16-byte column p%8
   const bf16_t* ap[MT];
   int a_lds[MT];
@@ -64,7 +79,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
     ap[i] = A + (size_t)m * K + c16 * 8;
     a_lds[i] = r * A_ROW_BYTES + c16 * 16;
   }
-  const int a_buf_bytes = MT * 32 * A_ROW_BYTES;
+  constexpr int A_BUF = MT * 32 * A_ROW_BYTES;
 
   f32x16_t acc[MT][NB];
 #pragma unroll
@@ -74,68 +89,74 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  uint4 wreg[D][NB][4];
-  uint4 areg[MT];
+  u32x4_t wreg[D][NB][4];
+  u32x4_t areg[D][MT];
 
-  // prologue: weights of the first D chunks, activations of the first chunk
+  // Every iteration issues the same loads (chunk indices past the split are clamped to its last
+  // chunk, an L2 hit, and their activations are zeroed so they add nothing): with a fixed number
+  // of loads in flight the compiler can wait for exactly the chunk it needs.
+  const int c_last = max(c_end - 1, c_begin);
+  const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+  // prologue: chunks c_begin .. c_begin+D-1
 #pragma unroll
   for (int u = 0; u < D; ++u) {
-    int c = c_begin + u;
-    if (c < c_end) {
+    const int c = c_begin + u;
+    const int cc = min(c, c_last);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+    for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * KC);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)c * (KC * 2 / 16) + s];
-    }
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)cc * W_CHUNK + s * W_STEP];
   }
-  if (c_begin < c_end) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) areg[i] = *reinterpret_cast<const uint4*>(ap[i] + (size_t)c_begin * KC);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) *reinterpret_cast<uint4*>(lds + a_lds[i]) = areg[i];
-  }
+  for (int i = 0; i < MT; ++i)
+    *reinterpret_cast<u32x4_t*>(lds + a_lds[i]) = c_begin < c_end ? areg[0][i] : zero4;
   __syncthreads();
 
-  for (int cb = c_begin; cb < c_end; cb += D) {
+  const int n_iter = (c_end - c_begin + D - 1) / D;   // groups of D chunks, the last one zero-padded
+  for (int it = 0; it < n_iter; ++it) {
 #pragma unroll
     for (int u = 0; u < D; ++u) {
-      const int c = cb + u;
-      if (c < c_end) {   // uniform over the workgroup
-        const int buf = (c - c_begin) & 1;
-        const bool more = c + 1 < c_end;
-        {
-          const int cn = more ? c + 1 : c;
+      const int c = c_begin + it * D + u;
+      const int buf = u & 1;                            // D is even
+      const unsigned char* abase = lds + buf * A_BUF + lr * A_ROW_BYTES + 64 * lg;
+      bf16x8_t af[2][MT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (s < 3) {
 #pragma unroll
           for (int i = 0; i < MT; ++i)
-            areg[i] = *reinterpret_cast<const uint4*>(ap[i] + (size_t)cn * KC);
+            af[(s + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES + 16 * (s + 1));
         }
-        const unsigned char* abase = lds + buf * a_buf_bytes + lr * A_ROW_BYTES + 64 * lg;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int i = 0; i < MT; ++i) {
 #pragma unroll
-          for (int i = 0; i < MT; ++i) {
-            bf16x8_t af = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES + 16 * s);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-              bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, wreg[u][nb][s]);
-              acc[i][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[i][nb], 0, 0, 0);
-            }
+          for (int nb = 0; nb < NB; ++nb) {
+            bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, wreg[u][nb][s]);
+            acc[i][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][i], bfr, acc[i][nb], 0, 0, 0);
           }
         }
-        // refill this ring slot with the chunk D ahead
-        if (c + D < c_end) {
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)(c + D) * (KC * 2 / 16) + s];
-        }
-        {
-#pragma unroll
-          for (int i = 0; i < MT; ++i)
-            *reinterpret_cast<uint4*>(lds + (buf ^ 1) * a_buf_bytes + a_lds[i]) = areg[i];
-        }
-        __syncthreads();
       }
+      // activations of chunk c+1 (ring slot u+1) -> the other LDS buffer
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        *reinterpret_cast<u32x4_t*>(lds + (buf ^ 1) * A_BUF + a_lds[i]) =
+            c + 1 < c_end ? areg[(u + 1) % D][i] : zero4;   // zeroed at use, not at load
+      // refill ring slot u with chunk c+D
+      {
+        const int cn = c + D;
+        const int cc = min(cn, c_last);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * KC);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)cc * W_CHUNK + s * W_STEP];
+      }
+      __syncthreads();
     }
   }
 
@@ -203,15 +224,30 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
     }
 }
 
-template <int MT, int NB>
+// row-major [N][K] -> tiles of 32 rows x 64 k stored as [chunk][row block][step][lane][8]
+__global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int N, int K) {
+  const size_t piece = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte piece
+  const size_t total = (size_t)N * K / 8;
+  if (piece >= total) return;
+  const int chunks = K / KC;
+  const int lane = piece & 63, s = (piece >> 6) & 3;
+  const size_t tile = piece >> 8;
+  const int nblk = N >> 5;
+  const int blk = (int)(tile % nblk);
+  const int c = (int)(tile / nblk);
+  const int n = blk * 32 + (lane & 31);
+  const int k = c * KC + 32 * (lane >> 5) + 8 * s;
+  reinterpret_cast<uint4*>(dst)[piece] = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
+}
+
+template <int MT, int NB, bool TILED = true, int D = 4>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
                        int N, int K, const GemmPlan& p) {
-  constexpr int D = 4;
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A, a_rows,
-                     (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
+                     a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
   return hipGetLastError();
 }
 
@@ -244,16 +280,25 @@ GemmPlan gemm_plan(int dtype, int M, int N, int K) {
   return p;
 }
 
+hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K) {
+  size_t pieces = (size_t)N * K / 8;
+  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const bf16_t*)src,
+                     (bf16_t*)dst, N, K);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
-                       float* out, int M, int N, int K, const GemmPlan& p) {
+                       float* out, int M, int N, int K, const GemmPlan& p, bool w_packed) {
   if (M <= 0) return hipSuccess;
   if (dtype == ESP_F32) {
     hipLaunchKernelGGL(k_gemm_f32, dim3(p.n_tiles, p.m_tiles), dim3(256), 0, st, (const float*)A, a_rows,
                        (const float*)W, out, M, N, K);
     return hipGetLastError();
   }
-#define ESP_GEMM_CASE(MT_, NB_) \
-  if (p.mt == MT_ && p.nb == NB_) return launch_bf16<MT_, NB_>(st, A, a_rows, W, out, M, N, K, p);
+#define ESP_GEMM_CASE(MT_, NB_)                                                                  \
+  if (p.mt == MT_ && p.nb == NB_)                                                                \
+    return w_packed ? launch_bf16<MT_, NB_, true>(st, A, a_rows, W, out, M, N, K, p)             \
+                    : launch_bf16<MT_, NB_, false>(st, A, a_rows, W, out, M, N, K, p);
   ESP_GEMM_CASE(1, 1)
   ESP_GEMM_CASE(2, 1)
   ESP_GEMM_CASE(3, 1)

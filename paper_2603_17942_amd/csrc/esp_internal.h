@@ -56,8 +56,10 @@ struct GemmPlan {
 GemmPlan gemm_plan(int dtype, int M, int N, int K);
 inline size_t gemm_out_elems(const GemmPlan& p, int M, int N) { return (size_t)p.splits * M * N; }
 // out: fp32 [splits][M][N].  a_rows (device, may be null): physical row of A for logical row m.
+// w_packed: W is in the streaming layout written by launch_pack_weight (bf16 only).
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
-                       float* out, int M, int N, int K, const GemmPlan& p);
+                       float* out, int M, int N, int K, const GemmPlan& p, bool w_packed);
+hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K);
 
 // ---- elementwise / glue (esp_elementwise.hip) ----------------------------------------------
 struct BlockDev {   // device-side view of esp_block + esp_kv scalars, passed by value

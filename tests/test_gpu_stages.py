@@ -35,6 +35,8 @@ def test_gemm_bf16(B, M, N, K):
     a = synth.normal_like((M, K), 1.0, 11, 0, "cuda", torch.bfloat16)
     w = synth.normal_like((N, K), 0.05, 11, 1, "cuda", torch.bfloat16)
     got = B.gemm(a, w).cpu().numpy()
+    got_packed = B.gemm(a, B.pack_weight(w), packed=True).cpu().numpy()
+    assert np.array_equal(got, got_packed)   # the streaming layout only moves bytes
     want = to_np(a) @ to_np(w).T            # fp64 on the same bf16 values
     # products of bf16 values are exact in fp32; only the accumulation order differs
     assert rel_err_rows(got, want) < 1e-5
