@@ -28,10 +28,10 @@ constexpr int KC = 64;            // k per chunk
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
 template <int MT, int NB, int D, bool TILED>   // D even
-__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
-                                                   const bf16_t* __restrict__ W, float* __restrict__ out, int M,
-                                                   int N, int K, int splits, int m_tiles, int n_tiles) {
-  extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
+__device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
+                                               const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
+                                               float* __restrict__ out, int M, int N, int K, int splits,
+                                               int m_tiles, int n_tiles) {
   // XCD-aware logical id: consecutive hardware ids go to different XCDs, so give each XCD a
   // contiguous range of tiles (tiles sharing weight rows then share an L2).
   const int total = m_tiles * n_tiles * splits;
@@ -121,23 +121,24 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
       const int c = c_begin + it * D + u;
       const int buf = u & 1;                            // D is even
       const unsigned char* abase = lds + buf * A_BUF + lr * A_ROW_BYTES + 64 * lg;
+      // Fragment reads run one MFMA step ahead and are pinned between the MFMA groups (scheduling
+      // barriers), so each read has MT*NB MFMAs of cover before its first use.
       bf16x8_t af[2][MT];
 #pragma unroll
       for (int i = 0; i < MT; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES);
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        if (s < 3) {
-#pragma unroll
-          for (int i = 0; i < MT; ++i)
-            af[(s + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES + 16 * (s + 1));
-        }
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
+          if (s < 3)
+            af[(s + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES + 16 * (s + 1));
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
             bf16x8_t bfr = __builtin_bit_cast(bf16x8_t, wreg[u][nb][s]);
             acc[i][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][i], bfr, acc[i][nb], 0, 0, 0);
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
       // activations of chunk c+1 (ring slot u+1) -> the other LDS buffer
@@ -176,6 +177,24 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
       }
     }
   }
+}
+
+// Two entry points over the same body: the large-tile one tells the compiler that one wave per
+// SIMD is all it will ever get, so it spends registers on prefetching instead of saving them.
+template <int MT, int NB, int D, bool TILED>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
+                                                   const bf16_t* __restrict__ W, float* __restrict__ out, int M,
+                                                   int N, int K, int splits, int m_tiles, int n_tiles) {
+  extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
+  gemm_bf16_body<MT, NB, D, TILED>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+}
+
+template <int MT, int NB, int D, bool TILED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_big(
+    const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
+    float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  gemm_bf16_body<MT, NB, D, TILED>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -240,14 +259,18 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
   reinterpret_cast<uint4*>(dst)[piece] = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
 }
 
-template <int MT, int NB, bool TILED = true, int D = 4>
+template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4)>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
                        int N, int K, const GemmPlan& p) {
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
-                     a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
+  if (MT * NB >= 8)
+    hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st,
+                       (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
+  else
+    hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
+                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
   return hipGetLastError();
 }
 
