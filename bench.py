@@ -128,6 +128,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the second layout")
     ap.add_argument("--kv-len", type=int, default=2048)
+    ap.add_argument("--fast-weights", action="store_true",
+                    help="draw the weights with torch.Tensor.normal_ (one kernel per tensor) instead of the "
+                         "counter-based generator; for counter-collection runs, where tens of thousands of "
+                         "generator dispatches only slow the profiler down")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -143,7 +147,23 @@ def main():
     shape = synth.SHAPES["llama3_8b"]
     n_nodes, k, K, kp, L = 64, 4, 8, 10, args.kv_len
     t_setup = time.perf_counter()
-    weights = synth.make_weights(shape, seed=1, device="cuda")
+    if args.fast_weights:
+        torch.manual_seed(1)
+        weights = synth.make_weights(shape.replace(n_layers=0), seed=1, device="cuda")
+        bf = dict(dtype=torch.bfloat16, device="cuda")
+        d, hd, ff = shape.d_model, shape.head_dim, shape.d_ff
+        nq, nkv = shape.n_q_heads * hd, shape.n_kv_heads * hd
+        for _ in range(shape.n_layers):
+            weights["layers"].append({
+                "wq": torch.empty((nq, d), **bf).normal_(0, 0.02), "wk": torch.empty((nkv, d), **bf).normal_(0, 0.02),
+                "wv": torch.empty((nkv, d), **bf).normal_(0, 0.02), "wo": torch.empty((d, nq), **bf).normal_(0, 0.02),
+                "w_gate": torch.empty((ff, d), **bf).normal_(0, 0.02),
+                "w_up": torch.empty((ff, d), **bf).normal_(0, 0.02),
+                "w_down": torch.empty((d, ff), **bf).normal_(0, 0.02),
+                "norm_attn": torch.ones(d, **bf), "norm_mlp": torch.ones(d, **bf),
+                "q_norm": torch.ones(hd, **bf), "k_norm": torch.ones(hd, **bf)})
+    else:
+        weights = synth.make_weights(shape, seed=1, device="cuda")
     prompt = synth.make_prompt(L + 1, shape.vocab, seed=2).tolist()
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup

@@ -251,8 +251,13 @@ def tree_forward(model: Model, blk: Block, mask_embed, k_cache, v_cache, cache_l
         h = h + (silu(gate) * up) @ as_f64(lw["w_down"]).T
     hidden = rmsnorm(h, w["final_norm"], model.rms_eps)
     rows = np.arange(R) if want_logits_rows is None else np.asarray(want_logits_rows, dtype=np.int64)
-    logits = hidden[rows] @ as_f64(w["lm_head"]).T
+    logits = lm_head_logits(model, hidden[rows])
     return logits, hidden, k_new, v_new
+
+
+def lm_head_logits(model: Model, hidden_rows: np.ndarray) -> np.ndarray:
+    """LM head on final-norm hidden states: logits = hidden @ lm_head^T (untied head)."""
+    return as_f64(hidden_rows) @ as_f64(model.weights["lm_head"]).T
 
 
 def sequence_forward(model: Model, embeds: np.ndarray, positions: Sequence[int],

@@ -1,0 +1,245 @@
+"""Parity at the workload sizes, in the launch configuration bench.py times.
+
+The oracle cannot run a 32-layer 8B-shaped decoder in test time, so each case keeps the full
+widths (d_model, heads, d_ff, vocabulary, KV length, tree size, rows) and cuts the depth to two
+layers; integer results are compared exactly where the oracle's margin exceeds the bf16 band.
+The KV cache contents are synthetic N(0,1)-like values (stand-in for a prefilled prompt).
+Long-context and ragged-batch attention are checked on sampled rows at full size."""
+import numpy as np
+import pytest
+import torch
+
+from util import O, oracle_model, small_shape, synth, to_np
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_17942_amd import binding
+    binding.load_library()
+    assert torch.cuda.is_available(), "GPU tests need a GPU; there is no fallback path"
+    return binding
+
+
+def rel_err_rows(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    den = np.max(np.abs(want), axis=-1, keepdims=True)
+    den[den == 0] = 1.0
+    return float(np.max(np.abs(got - want) / den))
+
+
+def decisive(row, tol=TOL):
+    top2 = np.sort(row)[-2:]
+    return (top2[1] - top2[0]) > 2 * tol * np.max(np.abs(row))
+
+
+@pytest.mark.parametrize("name,layout,n_nodes,k,K,kp,L", [
+    ("llama3_8b", 0, 64, 4, 8, 10, 2048),     # configs[1], block complexity (k+1) N = 320 rows
+    ("llama3_8b", 1, 64, 4, 8, 10, 2048),     # configs[1], root chain: 68 rows
+    ("qwen3_8b", 0, 96, 5, 10, 12, 4096),     # configs[2] shape: QK-norm, 576 rows
+])
+def test_step_at_full_width_two_layer_cut(B, name, layout, n_nodes, k, K, kp, L):
+    from paper_2603_17942_amd import decode
+    print(f"full-width step {name} layout={layout} N={n_nodes} k={k} L={L}", flush=True)
+    shape = synth.SHAPES[name].replace(n_layers=2)
+    w = synth.make_weights(shape, seed=1, device="cuda")
+    params = B.tree_params(n_nodes, k, K, 0, True, False, layout)
+    dec = decode.EspDecoder(shape, w, params, kp, [L + 1024], prefill_chunk=64)
+    kf, vf = synth.make_kv_fill(shape, L, seed=5, device="cuda")
+    for l in range(shape.n_layers):
+        dec.eng.kv_store(dec.kv, l, 0, 0, kf[l].contiguous(), vf[l].contiguous())
+    dec.kv.set_len([L])
+    tok, par = synth.make_random_tree(n_nodes, k, shape.vocab, seed=7)
+    dec.set_tree([tok.tolist()], [par.tolist()])
+    masks = synth.normal_like((k, shape.d_model), 0.02, 6, 0, "cuda", torch.bfloat16)
+    dec.mask_embed.copy_(masks)
+    R = dec.rows_per_seq
+    dec.logits_dbg = torch.zeros((R, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.step()
+    assert dec.eng.device_status() == 0
+    torch.cuda.synchronize()
+    print("gpu step done; oracle ...", flush=True)
+
+    m = oracle_model(shape, w)
+    blk = O.make_block(tok.numpy(), par.numpy(), k, layout)
+    assert blk.n_rows == R
+    kc = [to_np(kf[l]) for l in range(shape.n_layers)]
+    vc = [to_np(vf[l]) for l in range(shape.n_layers)]
+    _, hidden, k_new, v_new = O.tree_forward(m, blk, to_np(masks), kc, vc, L, want_logits_rows=[])
+    print("oracle forward done", flush=True)
+    # LM head at the tree rows -> verification
+    node_logits = O.lm_head_logits(m, hidden[:n_nodes])
+    lg = dec.logits_dbg[:n_nodes].cpu().numpy()
+    assert rel_err_rows(lg, node_logits) <= TOL
+    g = np.argmax(node_logits, axis=1)
+    g_gpu = dec.node_argmax[:n_nodes].cpu().numpy()
+    all_decisive = True
+    for r in range(n_nodes):
+        if decisive(node_logits[r]):
+            assert g_gpu[r] == g[r], r
+        else:
+            all_decisive = False
+    hid_gpu = to_np(dec.hidden[:R])
+    assert rel_err_rows(hid_gpu, hidden) <= TOL
+    if all_decisive:
+        n_star, accepted, emitted = O.verify_accept(blk.tok, blk.parent, g)
+        ne = int(dec.n_emit[0])
+        assert dec.emit_tok[0, :ne].tolist() == emitted
+        assert int(dec.star_row[0]) == n_star
+        assert int(dec.kv.len[0]) == L + ne
+        a = len(accepted)
+        rows = [blk.mask_row(n_star, j) for j in range(1, k + 1)] if layout == 0 else \
+            [blk.mask_row(0, a + i) for i in range(1, k - a + 1)]
+        mask_logits = O.lm_head_logits(m, hidden[rows])
+        assert rel_err_rows(dec.logits_dbg[rows].cpu().numpy(), mask_logits) <= TOL
+        ids_gpu = dec.topk_id[0].cpu().numpy()
+        ps_gpu = dec.topk_p[0].cpu().numpy()
+        same = True
+        for i, r in enumerate(rows):
+            ids, ps = O.softmax_topk(mask_logits[i], kp + 1)
+            np.testing.assert_allclose(ps_gpu[i], ps[:kp], rtol=0.5)
+            band = 2 * TOL * np.max(np.abs(mask_logits[i]))
+            v = mask_logits[i][ids]
+            for j in range(kp):
+                up = j == 0 or (v[j - 1] - v[j]) > band
+                down = (v[j] - v[j + 1]) > band
+                if up and down:
+                    assert ids_gpu[i, j] == ids[j], (i, j)
+                elif ids_gpu[i, j] != ids[j]:
+                    same = False
+        # committed K/V of root + accepted rows
+        keep = [0] + accepted
+        for l in range(shape.n_layers):
+            kk, vv = dec.eng.kv_load(dec.kv, l, 0, L, ne)
+            assert rel_err_rows(to_np(kk).reshape(ne, -1), k_new[l][keep].reshape(ne, -1)) <= TOL
+            assert rel_err_rows(to_np(vv).reshape(ne, -1), v_new[l][keep].reshape(ne, -1)) <= TOL
+        # the next tree is valid: full budget, ancestor closed, root = bonus token
+        nn = int(dec.cur.n_nodes[0])
+        assert nn == n_nodes and int(dec.cur.tok[0]) == emitted[-1]
+        par_next = dec.cur.parent[:nn].tolist()
+        assert par_next[0] == -1 and all(0 <= par_next[i] < i for i in range(1, nn))
+        if same:
+            lists_id = [O.softmax_topk(mask_logits[i], kp)[0] for i in range(len(rows))]
+            lists_p = [O.softmax_topk(mask_logits[i], kp)[1] for i in range(len(rows))]
+            nt, npar, _ = O.build_prune_tree(O.TreeParams(B=n_nodes, k=k, K=K, expand_width=0), lists_id, lists_p,
+                                             emitted[-1], n_depths=len(rows))
+            # same candidate lists: the tree can only differ if two cumulative probabilities tie to
+            # within the last bits of the two softmaxes
+            assert dec.cur.tok[:nn].tolist() == nt.tolist()
+            assert par_next == npar.tolist()
+    dec.eng.close()
+
+
+def test_long_context_attention_sampled_rows(B):
+    """configs[3]: L = 32768, tree 64 + 4 masks (68 rows) and the 320-row layout, one layer of the
+    Llama shape; the oracle evaluates a sample of rows (all heads) one by one."""
+    shape = synth.SHAPES["llama3_8b"].replace(n_layers=1, vocab=1024, d_ff=256)
+    w = synth.make_weights(shape, seed=1, device="cuda")
+    L = 32768
+    eng = B.Engine(shape, w, 1, 320, L + 1024)
+    kv = B.KvCache(shape, [L + 512])
+    kf, vf = synth.make_kv_fill(shape, L + 320, seed=5, device="cuda")
+    eng.kv_store(kv, 0, 0, 0, kf[0].contiguous(), vf[0].contiguous())
+    kv.set_len([L])
+    kn, vn = to_np(kf[0]), to_np(vf[0])
+    for layout, rows in [(1, 68), (0, 320)]:
+        print(f"long-context attention layout={layout}", flush=True)
+        tok, par = synth.make_random_tree(64, 4, shape.vocab, seed=9)
+        blk = B.BlockBuffers(1, rows, 4, layout)
+        blk.upload_trees([tok.tolist()], [par.tolist()])
+        eng.block_from_tree(blk)
+        q = synth.normal_like((rows, shape.n_q_heads, shape.head_dim), 1.0, 3, layout, "cuda", torch.bfloat16)
+        out = torch.zeros_like(q)
+        eng.attn_tree(blk, kv, 0, q, out)
+        assert eng.device_status() == 0
+        ob = O.make_block(tok.numpy(), par.numpy(), 4, layout)
+        sample = sorted(set([0, 1, 5, 37, 63, 64, 65, rows - 1]))
+        want = O.tree_attention(to_np(q)[sample], kn[:L], vn[:L], kn[L:L + rows], vn[L:L + rows],
+                                ob.visible[sample])
+        got = to_np(out)[sample]
+        assert rel_err_rows(got.reshape(-1, shape.head_dim), want.reshape(-1, shape.head_dim)) <= TOL
+    eng.close()
+
+
+def test_ragged_batch_attention_sampled_rows(B):
+    """configs[4]: 16 sequences, KV lengths uniform in [512, 8192], trees of 32..128 nodes with 4
+    mask tokens each (ragged pool); sampled rows of every sequence against the oracle."""
+    shape = synth.SHAPES["llama3_8b"].replace(n_layers=1, vocab=1024, d_ff=256)
+    w = synth.make_weights(shape, seed=1, device="cuda")
+    batch, k, layout = 16, 4, 1
+    lens = (512 + synth.uniform_ints(batch, 8192 - 512 + 1, 3, 0)).tolist()
+    nodes = (32 + synth.uniform_ints(batch, 128 - 32 + 1, 4, 0)).tolist()
+    rows = max(nodes) + k
+    eng = B.Engine(shape, w, batch, rows, max(lens) + rows + 64)
+    kv = B.KvCache(shape, [l + rows + 8 for l in lens])
+    trees = [synth.make_random_tree(nodes[b], 4, shape.vocab, seed=20 + b) for b in range(batch)]
+    blk = B.BlockBuffers(batch, rows, k, layout)
+    blk.upload_trees([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])
+    eng.block_from_tree(blk)
+    fills = []
+    for b in range(batch):
+        kf, vf = synth.make_kv_fill(shape, lens[b] + nodes[b] + k, seed=40 + b, device="cuda")
+        eng.kv_store(kv, 0, b, 0, kf[0].contiguous(), vf[0].contiguous())
+        fills.append((to_np(kf[0]), to_np(vf[0])))
+    kv.set_len(lens)
+    q = synth.normal_like((batch * rows, shape.n_q_heads, shape.head_dim), 1.0, 3, 7, "cuda", torch.bfloat16)
+    out = torch.zeros_like(q)
+    eng.attn_tree(blk, kv, 0, q, out)
+    assert eng.device_status() == 0
+    qn, on = to_np(q).reshape(batch, rows, shape.n_q_heads, -1), to_np(out).reshape(batch, rows, shape.n_q_heads, -1)
+    for b in range(batch):
+        R, L = nodes[b] + k, lens[b]
+        ob = O.make_block(trees[b][0].numpy(), trees[b][1].numpy(), k, layout)
+        sample = sorted(set([0, 1, nodes[b] // 2, nodes[b] - 1, nodes[b], R - 1]))
+        kn, vn = fills[b]
+        want = O.tree_attention(qn[b][sample], kn[:L], vn[:L], kn[L:L + R], vn[L:L + R], ob.visible[sample])
+        assert rel_err_rows(on[b][sample].reshape(-1, shape.head_dim), want.reshape(-1, shape.head_dim)) <= TOL
+        assert np.all(on[b][R:] == 0)
+    eng.close()
+
+
+def test_batched_step_against_oracle(B):
+    """Three independent sequences of different cache lengths and tree sizes in one block: every
+    entry point handles the batch dimension (small bf16 model, full oracle comparison)."""
+    from paper_2603_17942_amd import decode
+    shape = small_shape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=512, vocab=2048, n_layers=2,
+                        dtype="bf16", rope_theta=5.0e5)
+    w = synth.make_weights(shape, seed=28, unit_gains=False)
+    m = oracle_model(shape, w)
+    k, K, kp, Bn, layout = 3, 4, 6, 24, 0
+    lens, nodes = [300, 64, 1000], [24, 9, 17]
+    params = B.tree_params(Bn, k, K, 0, True, False, layout)
+    dec = decode.EspDecoder(shape, w, params, kp, [l + 512 for l in lens], prefill_chunk=64)
+    fills = []
+    for b in range(3):
+        kf, vf = synth.make_kv_fill(shape, lens[b], seed=30 + b, device="cuda")
+        for l in range(shape.n_layers):
+            dec.eng.kv_store(dec.kv, l, b, 0, kf[l].contiguous(), vf[l].contiguous())
+        fills.append((kf, vf))
+    dec.kv.set_len(lens)
+    trees = [synth.make_random_tree(nodes[b], k, shape.vocab, seed=50 + b) for b in range(3)]
+    dec.set_tree([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])
+    masks = synth.normal_like((k, shape.d_model), 0.02, 12, 0, "cuda", torch.bfloat16)
+    dec.mask_embed.copy_(masks)
+    R = dec.rows_per_seq
+    dec.logits_dbg = torch.zeros((3 * R, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.step()
+    assert dec.eng.device_status() == 0
+    lg = dec.logits_dbg.cpu().numpy()
+    emitted = dec.emitted()
+    for b in range(3):
+        kf, vf = fills[b]
+        st = O.DecodeState([to_np(kf[l]) for l in range(shape.n_layers)], [to_np(vf[l]) for l in range(shape.n_layers)],
+                           lens[b], trees[b][0].numpy().astype(np.int64), trees[b][1].numpy().astype(np.int64),
+                           to_np(masks))
+        res = O.esp_step(m, st, O.TreeParams(B=Bn, k=k, K=K, expand_width=0), layout, kp, "bf16")
+        rb = res.logits.shape[0]
+        assert rel_err_rows(lg[b * R:b * R + rb], res.logits) <= TOL
+        if all(decisive(res.logits[r]) for r in range(nodes[b])):
+            assert emitted[b] == res.emitted
+            assert int(dec.star_row[b]) == res.n_star
+            assert int(dec.kv.len[b]) == st.cache_len
+            assert int(dec.cur.n_nodes[b]) == len(res.next_tok)
+    dec.eng.close()
