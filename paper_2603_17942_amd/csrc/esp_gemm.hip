@@ -18,6 +18,8 @@
 //    order, so a row's result does not depend on how many other rows the block holds.
 //
 // fp32 path (tiny configuration): plain LDS-tiled FMA kernel with bounds checks, row-major weights.
+#include <algorithm>
+
 #include "esp_internal.h"
 
 namespace {
@@ -27,7 +29,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int KC = 64;            // k per chunk
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
-template <int MT, int NB, int D, bool TILED>   // D even
+template <int MT, int NB, int D, bool TILED, int WM>   // D even; WM wave groups along M
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
@@ -44,8 +46,10 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int lr = lane & 31, lg = lane >> 5;
-  const int m0 = mi * (MT * 32);
-  const int n0 = ni * (128 * NB) + wave * (32 * NB);
+  const int wn = wave & 3, wm = wave >> 2;       // column group, row group of this wave
+  const int mt0 = mi * (WM * MT * 32);           // first row of the workgroup tile
+  const int m0 = mt0 + wm * (MT * 32);           // first row of this wave
+  const int n0 = ni * (128 * NB) + wn * (32 * NB);
 
   const int chunks = K / KC;
   const int cps = (chunks + splits - 1) / splits;
@@ -72,14 +76,14 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   int a_lds[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    int p = tid + 256 * i;
+    int p = tid + 256 * WM * i;
     int r = p >> 3, c16 = p & 7;
-    int m = min(m0 + r, M - 1);
+    int m = min(mt0 + r, M - 1);
     if (a_rows) m = max(a_rows[m], 0);
     ap[i] = A + (size_t)m * K + c16 * 8;
     a_lds[i] = r * A_ROW_BYTES + c16 * 16;
   }
-  constexpr int A_BUF = MT * 32 * A_ROW_BYTES;
+  constexpr int A_BUF = WM * MT * 32 * A_ROW_BYTES;
 
   f32x16_t acc[MT][NB];
 #pragma unroll
@@ -120,7 +124,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
     for (int u = 0; u < D; ++u) {
       const int c = c_begin + it * D + u;
       const int buf = u & 1;                            // D is even
-      const unsigned char* abase = lds + buf * A_BUF + lr * A_ROW_BYTES + 64 * lg;
+      const unsigned char* abase = lds + buf * A_BUF + (wm * MT * 32 + lr) * A_ROW_BYTES + 64 * lg;
       // Fragment reads run one MFMA step ahead and are pinned between the MFMA groups (scheduling
       // barriers), so each read has MT*NB MFMAs of cover before its first use.
       bf16x8_t af[2][MT];
@@ -179,14 +183,16 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   }
 }
 
-// Two entry points over the same body: the large-tile one tells the compiler that one wave per
-// SIMD is all it will ever get, so it spends registers on prefetching instead of saving them.
+// Two entry points over the same body.  The small-tile one (<= 4 row tiles, one column block per
+// wave) leaves occupancy to the compiler.  The large-tile one tells it that one wave per SIMD is
+// all it will ever get, so registers go to prefetching.  (A 512-thread variant with two row groups
+// per workgroup and two waves per SIMD was measured and was not faster.)
 template <int MT, int NB, int D, bool TILED>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
                                                    int N, int K, int splits, int m_tiles, int n_tiles) {
   extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
-  gemm_bf16_body<MT, NB, D, TILED>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+  gemm_bf16_body<MT, NB, D, TILED, 1>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
 }
 
 template <int MT, int NB, int D, bool TILED>
@@ -194,7 +200,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
     float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_bf16_body<MT, NB, D, TILED>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+  gemm_bf16_body<MT, NB, D, TILED, 1>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -278,28 +284,29 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
 
 GemmPlan gemm_plan(int dtype, int M, int N, int K) {
   GemmPlan p;
+  p.wm = 1;
   if (dtype == ESP_F32) {
     p.splits = 1; p.mt = 2; p.nb = 2; p.m_tiles = (M + 63) / 64; p.n_tiles = (N + 63) / 64;
     return p;
   }
-  // split-K from (N, K) only: aim at >= 256 workgroups of 128 columns, at least 8 chunks each
-  int cols128 = (N + 127) / 128;
-  int s = (256 + cols128 - 1) / cols128;
-  int max_s = K / (KC * 8);
-  if (max_s < 1) max_s = 1;
-  if (s > max_s) s = max_s;
-  if (s > 8) s = 8;
-  if (s < 1) s = 1;
-  p.splits = s;
-  int tiles32 = (M + 31) / 32;
+  const int tiles32 = (M + 31) / 32;
+  const int max_s = std::max(1, K / (KC * 8));    // at least 8 chunks per split
   if (tiles32 <= 4) {
+    // up to 128 rows: one row tile per workgroup, 128 columns, several workgroups per CU.
+    // split-K from (N, K) only: aim at >= 256 workgroups
     p.mt = tiles32; p.nb = 1; p.m_tiles = 1;
+    p.n_tiles = (N + 127) / 128;
+    p.splits = std::min(std::min((256 + p.n_tiles - 1) / p.n_tiles, max_s), 8);
   } else {
+    // more rows: up to 5 row tiles and 256 columns per workgroup, one workgroup per CU (the
+    // accumulators fill the register file); split-K fills the 256 CUs without spilling into a
+    // second, mostly empty round (measured: 240 workgroups beat 288 by 1.6x on the QKV shape)
     p.nb = 2;
     p.m_tiles = (tiles32 + 4) / 5;
     p.mt = (tiles32 + p.m_tiles - 1) / p.m_tiles;
+    p.n_tiles = (N + 255) / 256;
+    p.splits = std::max(1, std::min(std::min(256 / (p.m_tiles * p.n_tiles), max_s), 8));
   }
-  p.n_tiles = (N + 128 * p.nb - 1) / (128 * p.nb);
   return p;
 }
 

@@ -47,11 +47,12 @@ __host__ __device__ __forceinline__ size_t v_off(int64_t slot, int d, int hd) {
 
 // ---- GEMM -----------------------------------------------------------------------------------
 struct GemmPlan {
-  int splits;        // split-K factor; depends on (N, K) only, never on M
+  int splits;        // split-K factor; a function of (N, K) and of the tile class (<=128 rows or more)
   int mt;            // 32-row MFMA tiles per workgroup
   int nb;            // 32-column blocks per wave
   int m_tiles;       // workgroup tiles along M
   int n_tiles;       // workgroup tiles along N
+  int wm;            // wave groups along M inside a workgroup (1: 256 threads, 2: 512 threads)
 };
 GemmPlan gemm_plan(int dtype, int M, int N, int K);
 inline size_t gemm_out_elems(const GemmPlan& p, int M, int N) { return (size_t)p.splits * M * N; }
