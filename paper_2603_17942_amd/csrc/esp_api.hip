@@ -368,10 +368,18 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     if (p_lm.splits != 1) return ESP_ESHAPE;
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b)); }
-    { ESP_PROF(ESP_SITE_LM_HEAD);
-      ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm, pk)); }
-    { ESP_PROF(ESP_SITE_GLUE);
-      ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b)); }
+    if (gemm_argmax_supported(dt, Mn, m.vocab, d) &&
+        gemm_argmax_scratch_floats(Mn, m.vocab) <= c->logits_rows * (size_t)m.vocab) {
+      // arg-max in the GEMM epilogue: the [rows, vocab] logits are never written
+      ESP_PROF(ESP_SITE_LM_HEAD);
+      ESP_HIP(launch_gemm_argmax(s, hidden_out, c->idx_a, c->lm_head, Mn, m.vocab, d, c->logits, node_argmax,
+                                 c->idx_b));
+    } else {
+      { ESP_PROF(ESP_SITE_LM_HEAD);
+        ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm, pk)); }
+      { ESP_PROF(ESP_SITE_GLUE);
+        ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b)); }
+    }
   }
   return ESP_OK;
 }

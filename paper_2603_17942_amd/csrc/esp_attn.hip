@@ -17,6 +17,8 @@
 //
 // Generic path (k_attn_generic): one wave per (row, head, split), any dtype / head_dim multiple of
 // 64; used by the fp32 tiny configuration.
+#include <algorithm>
+
 #include "esp_internal.h"
 
 namespace {
@@ -148,7 +150,8 @@ __device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char
 template <int W>
 __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, int layer, int hq, int hkv,
                                                       const bf16_t* __restrict__ q, float* __restrict__ part_o,
-                                                      float* __restrict__ part_ml, int nsplit, int tps) {
+                                                      float* __restrict__ part_ml, int nsplit, int tps,
+                                                      int q_tiles) {
   constexpr int HD = 128;
   constexpr int NT = 64 * W;
   constexpr int PIECES = (1024 + NT - 1) / NT;   // 16-byte pieces per thread and tile, K and V alike
@@ -158,15 +161,25 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 31, lg = lane >> 5;
   const int G = hq / hkv;
-  const int seq = blockIdx.z / nsplit, sp = blockIdx.z % nsplit, kvh = blockIdx.y;
+  // XCD-aware logical id (hardware ids go round-robin over the 8 XCDs): the query tiles that
+  // stream the same keys (same kv head, same split) get consecutive logical ids on one XCD and
+  // so share its L2.
+  const int total_wg = q_tiles * hkv * b.batch * nsplit;
+  const int per_xcd = (total_wg + 7) >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= total_wg) return;
+  const int qt = logical % q_tiles;
+  const int kvh = (logical / q_tiles) % hkv;
+  const int zz = logical / (q_tiles * hkv);
+  const int seq = zz / nsplit, sp = zz % nsplit;
   const int nr = b.n_rows[seq];
   if (!seq_ok(kv, seq, nr, b.rows_per_seq)) return;
-  if (blockIdx.x * (W * 32) >= nr * G) return;          // no live query column in this workgroup
+  if (qt * (W * 32) >= nr * G) return;                  // no live query column in this workgroup
   const int L = kv.len[seq], total = L + nr;
   const int ntiles = (total + 63) >> 6;
   const int t0 = sp * tps, t1 = min(ntiles, t0 + tps);
 
-  const int qcol = (blockIdx.x * W + wave) * 32 + lr;
+  const int qcol = (qt * W + wave) * 32 + lr;
   const bool col_live = qcol < nr * G;
   const int r = col_live ? qcol / G : 0;
   const int h = kvh * G + (col_live ? qcol % G : 0);
@@ -356,16 +369,17 @@ __global__ void k_attn_merge(BlockDev b, KvDev kv, int hq, int hd, const float* 
 }  // namespace
 
 AttnPlan attn_plan(int batch, int rows_per_seq, int hq, int hkv, int len_bound) {
+  // Splits of the key range: enough workgroups for ~1.5 per CU, but no more -- every split
+  // writes a partial (m, l, O) per query row and head that the merge kernel reads back -- and
+  // at least 3 key tiles of 64 per split.
   AttnPlan p;
   int nt = (len_bound + rows_per_seq + 63) / 64;
   int G = hq / hkv;
   int qtiles = (rows_per_seq * G + 127) / 128;
   int base = qtiles * hkv * batch;
-  int want = (768 + base - 1) / base;
-  int max_by_len = (nt + 1) / 2;      // at least 2 key tiles per split
-  int ns = want < max_by_len ? want : max_by_len;
-  if (ns < 1) ns = 1;
-  if (ns > 64) ns = 64;
+  int want = (384 + base - 1) / base;
+  int max_by_len = std::max(1, nt / 3);
+  int ns = std::max(1, std::min(std::min(want, max_by_len), 64));
   p.tiles_per_split = (nt + ns - 1) / ns;
   p.nsplit = (nt + p.tiles_per_split - 1) / p.tiles_per_split;
   return p;
@@ -390,7 +404,9 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
       int pad = ((wave_tiles + w - 1) / w) * w - wave_tiles;
       if (pad < best_pad) { best_pad = pad; W = w; }
     }
-    dim3 grid((wave_tiles + W - 1) / W, hkv, b.batch * p.nsplit);
+    const int q_tiles = (wave_tiles + W - 1) / W;
+    const int total_wg = q_tiles * hkv * b.batch * p.nsplit;
+    dim3 grid(((total_wg + 7) / 8) * 8);
     size_t lds = 2 * (size_t)(K_TILE_BYTES + V_TILE_BYTES);
     // more than 64 KB of dynamic LDS must be granted per kernel once
     static bool lds_granted = false;
@@ -411,7 +427,7 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
 #define ESP_ATTN_CASE(w)                                                                                  \
   case w:                                                                                                 \
     hipLaunchKernelGGL(k_attn_mfma<w>, grid, dim3(64 * w), lds, st, b, kv, layer, hq, hkv, (const bf16_t*)q, \
-                       part_o, part_ml, p.nsplit, p.tiles_per_split);                                     \
+                       part_o, part_ml, p.nsplit, p.tiles_per_split, q_tiles);                            \
     break;
     switch (W) {
       ESP_ATTN_CASE(2)

@@ -29,7 +29,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int KC = 64;            // k per chunk
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
-template <int MT, int NB, int D, bool TILED, int WM>   // D even; WM wave groups along M
+template <int MT, int NB, int D, bool TILED, int WM, bool AMAX>   // D even; WM wave groups along M
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
@@ -166,18 +166,66 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   }
 
   // epilogue: lane holds column n, rows 8*(v/4) + 4*lg + v%4 of each 32x32 tile
-  float* o = out + (size_t)z * M * N;
+  if (!AMAX) {
+    float* o = out + (size_t)z * M * N;
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int n = n0 + nb * 32 + lr;
-    if (n0 + nb * 32 < N) {
+    for (int nb = 0; nb < NB; ++nb) {
+      const int n = n0 + nb * 32 + lr;
+      if (n0 + nb * 32 < N) {
 #pragma unroll
-      for (int i = 0; i < MT; ++i) {
+        for (int i = 0; i < MT; ++i) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int m = m0 + i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-          if (m < M) o[(size_t)m * N + n] = acc[i][nb][v];
+          for (int v = 0; v < 16; ++v) {
+            int m = m0 + i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+            if (m < M) o[(size_t)m * N + n] = acc[i][nb][v];
+          }
         }
+      }
+    }
+  } else {
+    // arg-max epilogue (LM head at the tree rows; needs splits == 1): per row the maximum over
+    // this workgroup's columns, lowest column on ties.  `out` receives [n_tiles][M] pairs
+    // (value, column as int bits); the logits themselves are never written.
+    float* red = reinterpret_cast<float*>(lds);            // [4 waves][MT*32 rows][2]
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float best = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int n = n0 + nb * 32 + lr;
+          const float x = acc[i][nb][v];
+          if (n0 + nb * 32 < N && (x > best || (x == best && n < bi))) { best = x; bi = n; }
+        }
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {                  // over the 32 columns of a lane half
+          float ov = __shfl_xor(best, o, 64);
+          int oi = __shfl_xor(bi, o, 64);
+          if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        }
+        if (lr == 0) {
+          const int rl = i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+          red[(wn * MT * 32 + rl) * 2 + 0] = best;
+          red[(wn * MT * 32 + rl) * 2 + 1] = __int_as_float(bi);
+        }
+      }
+    }
+    __syncthreads();
+    for (int rl = tid; rl < MT * 32; rl += 256) {
+      float best = red[rl * 2];
+      int bi = __float_as_int(red[rl * 2 + 1]);
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        float ov = red[(w * MT * 32 + rl) * 2];
+        int oi = __float_as_int(red[(w * MT * 32 + rl) * 2 + 1]);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+      }
+      const int m = mt0 + rl;
+      if (m < M) {
+        out[((size_t)ni * M + m) * 2 + 0] = best;
+        out[((size_t)ni * M + m) * 2 + 1] = __int_as_float(bi);
       }
     }
   }
@@ -187,12 +235,12 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
 // wave) leaves occupancy to the compiler.  The large-tile one tells it that one wave per SIMD is
 // all it will ever get, so registers go to prefetching.  (A 512-thread variant with two row groups
 // per workgroup and two waves per SIMD was measured and was not faster.)
-template <int MT, int NB, int D, bool TILED>
+template <int MT, int NB, int D, bool TILED, bool AMAX>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
                                                    int N, int K, int splits, int m_tiles, int n_tiles) {
   extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
-  gemm_bf16_body<MT, NB, D, TILED, 1>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+  gemm_bf16_body<MT, NB, D, TILED, 1, AMAX>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
 }
 
 template <int MT, int NB, int D, bool TILED>
@@ -200,7 +248,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
     float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_bf16_body<MT, NB, D, TILED, 1>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+  gemm_bf16_body<MT, NB, D, TILED, 1, false>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -265,7 +313,7 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
   reinterpret_cast<uint4*>(dst)[piece] = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
 }
 
-template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4)>
+template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), bool AMAX = false>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
                        int N, int K, const GemmPlan& p) {
   int total = p.m_tiles * p.n_tiles * p.splits;
@@ -275,7 +323,7 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
     hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st,
                        (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
   else
-    hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
+    hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, AMAX>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
                        a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
   return hipGetLastError();
 }
@@ -308,6 +356,64 @@ GemmPlan gemm_plan(int dtype, int M, int N, int K) {
     p.splits = std::max(1, std::min(std::min(256 / (p.m_tiles * p.n_tiles), max_s), 8));
   }
   return p;
+}
+
+namespace {
+
+// arg-max over the per-tile partials written by the AMAX epilogue: one workgroup per row
+__global__ __launch_bounds__(256) void k_argmax_tiles(const float* __restrict__ part, int n_tiles, int M,
+                                                      int32_t* __restrict__ out, const int32_t* __restrict__ out_index) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int m = blockIdx.x;
+  const int dst = out_index ? out_index[m] : m;
+  if (dst < 0) return;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int t = threadIdx.x; t < n_tiles; t += 256) {
+    float v = part[((size_t)t * M + m) * 2];
+    int i = __float_as_int(part[((size_t)t * M + m) * 2 + 1]);
+    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(best, o, 64);
+    int oi = __shfl_xor(bi, o, 64);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+    out[dst] = bi == 0x7fffffff ? 0 : bi;
+  }
+}
+
+}  // namespace
+
+// LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows):
+// scratch holds n_tiles * M (value, column) pairs; out[out_index[m]] = arg-max of row m.
+bool gemm_argmax_supported(int dtype, int M, int N, int K) {
+  if (dtype != ESP_BF16) return false;
+  GemmPlan p = gemm_plan(dtype, M, N, K);
+  return p.nb == 1 && p.splits == 1 && p.m_tiles == 1;
+}
+size_t gemm_argmax_scratch_floats(int M, int N) { return (size_t)((N + 127) / 128) * M * 2; }
+
+hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
+                              int K, float* scratch, int32_t* out, const int32_t* out_index) {
+  GemmPlan p = gemm_plan(ESP_BF16, M, N, K);
+  hipError_t e = hipErrorInvalidValue;
+  switch (p.mt) {
+    case 1: e = launch_bf16<1, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
+    case 2: e = launch_bf16<2, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
+    case 3: e = launch_bf16<3, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
+    case 4: e = launch_bf16<4, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
+  }
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_argmax_tiles, dim3(M), dim3(256), 0, st, scratch, p.n_tiles, M, out, out_index);
+  return hipGetLastError();
 }
 
 hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K) {

@@ -61,6 +61,11 @@ inline size_t gemm_out_elems(const GemmPlan& p, int M, int N) { return (size_t)p
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
                        float* out, int M, int N, int K, const GemmPlan& p, bool w_packed);
 hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K);
+// LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows, one split)
+bool gemm_argmax_supported(int dtype, int M, int N, int K);
+size_t gemm_argmax_scratch_floats(int M, int N);
+hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
+                              int K, float* scratch, int32_t* out, const int32_t* out_index);
 
 // ---- elementwise / glue (esp_elementwise.hip) ----------------------------------------------
 struct BlockDev {   // device-side view of esp_block + esp_kv scalars, passed by value
