@@ -69,9 +69,8 @@ __global__ __launch_bounds__(64) void k_attn_generic(BlockDev b, KvDev kv, int l
     }
     float s = NEG_BIG;
     if (valid) {
-      const T* kr = kp + k_off(base + key, 0, HD);
       float acc = 0.f;
-      for (int d = 0; d < HD; ++d) acc = fmaf(to_f32(kr[d]), qs[d], acc);
+      for (int d = 0; d < HD; ++d) acc = fmaf(to_f32(kp[k_off(base + key, d, HD)]), qs[d], acc);
       s = acc;
     }
     float m_new = fmaxf(m, wave_max(s));
@@ -85,8 +84,7 @@ __global__ __launch_bounds__(64) void k_attn_generic(BlockDev b, KvDev kv, int l
 #pragma unroll
     for (int i = 0; i < HD / 64; ++i) {
       float a = o[i] * alpha;
-      const T* vr = vp + v_off(base + t * 64, lane + 64 * i, HD);
-      for (int kk = 0; kk < nk; ++kk) a = fmaf(ps[kk], to_f32(vr[kk]), a);
+      for (int kk = 0; kk < nk; ++kk) a = fmaf(ps[kk], to_f32(vp[v_off(base + t * 64 + kk, lane + 64 * i, HD)]), a);
       o[i] = a;
     }
     __syncthreads();
@@ -101,23 +99,23 @@ __global__ __launch_bounds__(64) void k_attn_generic(BlockDev b, KvDev kv, int l
 }
 
 // --------------------------------------------------------------------------------------------------
-constexpr int K_ROW = 272;   // LDS bytes per key row: 256 + 16 (ds_read_b128 conflict-free over 8 rows)
-constexpr int V_ROW = 136;   // LDS bytes per feature row: 128 + 8 (ds_read_b64 conflict-free over 16 rows)
-constexpr int K_TILE_BYTES = 64 * K_ROW;
-constexpr int V_TILE_BYTES = 128 * V_ROW;
+constexpr int K_TILE_BYTES = 64 * 128 * 2;   // 64 keys: two cache blocks of 32 slots, 16 fragments of 1 KB
+constexpr int V_TILE_BYTES = 64 * 128 * 2;
 
-// Tile staging.  Loads are unconditional (a piece index past the tile is clamped and its value
-// dropped at the store) so that the staging registers stay in VGPRs.
+// Tile staging: a tile of 64 keys is 16 KB of K and 16 KB of V, both contiguous in the cache and
+// already in fragment order, so staging is a linear copy.  Loads are unconditional (a piece index
+// past the tile is clamped and its value dropped at the store) so the staging registers stay in
+// VGPRs.
 template <int W>
 __device__ __forceinline__ void attn_load_tile(const bf16_t* __restrict__ kt, const bf16_t* __restrict__ vt, int tid,
-                                               uint4 (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
-                                               uint4 (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
+                                               u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
+                                               u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
   constexpr int NT = 64 * W, PIECES = (1024 + NT - 1) / NT;
 #pragma unroll
   for (int i = 0; i < PIECES; ++i) {
     int p = min(tid + NT * i, 1023);
-    kreg[i] = *reinterpret_cast<const uint4*>(kt + (size_t)p * 8);
-    vreg[i] = *reinterpret_cast<const uint4*>(vt + (size_t)p * 8);
+    kreg[i] = *reinterpret_cast<const u32x4_t*>(kt + (size_t)p * 8);
+    vreg[i] = *reinterpret_cast<const u32x4_t*>(vt + (size_t)p * 8);
   }
 }
 
@@ -125,26 +123,48 @@ __device__ __forceinline__ void attn_load_tile(const bf16_t* __restrict__ kt, co
 // probability is zero, but 0 * NaN from never-written cache memory would poison the MFMA)
 template <int W>
 __device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char* vs, int tid, int keys_left,
-                                                const uint4 (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
-                                                const uint4 (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
+                                                const u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
+                                                const u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
   constexpr int NT = 64 * W, PIECES = (1024 + NT - 1) / NT;
 #pragma unroll
   for (int i = 0; i < PIECES; ++i) {
     int p = tid + NT * i;
     if (p < 1024) {
-      *reinterpret_cast<uint4*>(ks + (p >> 4) * K_ROW + (p & 15) * 16) = kreg[i];
-      uint4 v = vreg[i];
-      const int nv = keys_left - (p & 7) * 8;   // valid keys among the 8 of this piece
-      // word w holds keys 2w (low half) and 2w+1 (high half)
-      v.x &= nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
-      v.y &= nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
-      v.z &= nv >= 6 ? 0xffffffffu : (nv == 5 ? 0x0000ffffu : 0u);
-      v.w &= nv >= 8 ? 0xffffffffu : (nv == 7 ? 0x0000ffffu : 0u);
-      unsigned char* dst = vs + (p >> 3) * V_ROW + (p & 7) * 16;
-      *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.y);
-      *reinterpret_cast<uint2*>(dst + 8) = make_uint2(v.z, v.w);
+      *reinterpret_cast<u32x4_t*>(ks + p * 16) = kreg[i];
+      u32x4_t v = vreg[i];
+      if (keys_left < 64) {                     // last tile of the sequence only (uniform branch)
+        // piece p = fragment (block p/512, key-step (p/64)%2) of lane p%64; word w holds elements
+        // 2w, 2w+1 = keys k0, k0+1
+        const int kbase = (p >> 9) * 32 + ((p >> 6) & 1) * 16 + ((p >> 5) & 1) * 4;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int k0 = kbase + 8 * (w >> 1) + 2 * (w & 1);
+          v[w] &= k0 + 1 < keys_left ? 0xffffffffu : (k0 < keys_left ? 0x0000ffffu : 0u);
+        }
+      }
+      *reinterpret_cast<u32x4_t*>(vs + p * 16) = v;
     }
   }
+}
+
+// Visibility bits of 64 consecutive keys for one block row: bit j stands for block position
+// c_lo + j (negative positions are committed cache slots, always visible; positions from
+// keys_in_tile on lie past the sequence).  anc is the row's ancestor bitset.
+__device__ __forceinline__ uint64_t key_window(const uint64_t* __restrict__ anc, int anc_words, int c_lo,
+                                               int keys_in_tile) {
+  uint64_t wnd;
+  if (c_lo < 0) {
+    const int n = -c_lo;                                   // 1..63 cache keys lead the tile
+    const uint64_t a0 = anc_words > 0 ? anc[0] : 0ull;
+    wnd = (a0 << n) | ((1ull << n) - 1ull);
+  } else {
+    const int w0 = c_lo >> 6, sh = c_lo & 63;
+    const uint64_t a0 = w0 < anc_words ? anc[w0] : 0ull;
+    const uint64_t a1 = w0 + 1 < anc_words ? anc[w0 + 1] : 0ull;
+    wnd = sh ? (a0 >> sh) | (a1 << (64 - sh)) : a0;
+  }
+  if (keys_in_tile < 64) wnd &= (1ull << keys_in_tile) - 1ull;
+  return wnd;
 }
 
 template <int W>
@@ -208,7 +228,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
   const int64_t base = kv.base[seq];
   const float scale = LOG2E / sqrtf((float)HD);
 
-  uint4 kreg[PIECES], vreg[PIECES];
+  u32x4_t kreg[PIECES], vreg[PIECES];
 
   f32x16_t oacc[4];
 #pragma unroll
@@ -217,9 +237,9 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
     for (int v = 0; v < 16; ++v) oacc[i][v] = 0.f;
   float m = NEG_BIG, l = 0.f;
 
-  // K tile t: 64 rows of 256 B, contiguous; V tile t: [128][64], contiguous
+  // tile t of K and of V: 64 * HD elements each, contiguous (two cache blocks)
   const bf16_t* kt0 = kp + (size_t)base * HD;
-  const bf16_t* vt0 = vp + (size_t)(base >> 6) * HD * 64;
+  const bf16_t* vt0 = vp + (size_t)base * HD;
   attn_load_tile<W>(kt0 + (size_t)t0 * 64 * HD, vt0 + (size_t)t0 * 64 * HD, tid, kreg, vreg);
   attn_store_tile<W>(ks, vs, tid, total - t0 * 64, kreg, vreg);
   __syncthreads();
@@ -238,88 +258,105 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
-    const unsigned char* kbase = ks + buf * K_TILE_BYTES + lr * K_ROW + 16 * lg;
+    // Fragment reads run one group (4 reads, 4 MFMAs) ahead of their use and are pinned there by
+    // scheduling barriers: left to itself the compiler funnels every read through one register
+    // quad and waits out the full LDS latency before each MFMA.
+    const unsigned char* kbase = ks + buf * K_TILE_BYTES + lane * 16;   // fragment (kb, s) at (kb*8 + s) KB
+    bf16x8_t fr[2][4];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int j = 0; j < 4; ++j)   // group g holds steps 2g, 2g+1 of both key blocks: j = 2*(s&1) + kb
+      fr[0][j] = *reinterpret_cast<const bf16x8_t*>(kbase + ((j & 1) * 8 + (j >> 1)) * 1024);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kbase + kb * 32 * K_ROW + 32 * s);
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[kb], 0, 0, 0);
+    for (int g = 0; g < 4; ++g) {
+      if (g < 3) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          fr[(g + 1) & 1][j] =
+              *reinterpret_cast<const bf16x8_t*>(kbase + ((j & 1) * 8 + 2 * (g + 1) + (j >> 1)) * 1024);
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[2 * g + (j >> 1)], sacc[j & 1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // register v of block kb <-> key kb*32 + 8*(v/4) + 4*lg + v%4
-    float tmax = NEG_BIG;
+    // register v of block kb <-> key kb*32 + 8*(v/4) + 4*lg + v%4.  Scores stay unscaled; the
+    // scale is folded into the exponent: p = 2^(s*scale - m*scale).
     const int key0 = t * 64;
-    if (key0 + 64 <= L) {   // tile inside the committed cache: no mask
+    const bool masked_tile = key0 + 64 > L;   // tiles inside the committed cache need no mask
+    if (masked_tile) {
+      // visibility of the tile's 64 keys for this lane's row, bit j <-> key key0 + j
+      const uint64_t wnd = key_window(anc, b.anc_words, key0 - L, total - key0);
+      const unsigned wlo = (unsigned)wnd >> (4 * lg), whi = (unsigned)(wnd >> 32) >> (4 * lg);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          sacc[kb][v] *= scale;
-          tmax = fmaxf(tmax, sacc[kb][v]);
-        }
-    } else {
-      const int c_lo = key0 - L;
-      const int w0 = (c_lo > 0 ? c_lo : 0) >> 6;
-      const uint64_t a0 = w0 < b.anc_words ? anc[w0] : 0ull;
-      const uint64_t a1 = w0 + 1 < b.anc_words ? anc[w0 + 1] : 0ull;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int key = key0 + kb * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-          int c = key - L;
-          bool valid = c < 0;
-          if (c >= 0 && key < total) {
-            uint64_t word = (c >> 6) == w0 ? a0 : a1;
-            valid = (word >> (c & 63)) & 1ull;
-          }
-          float sv = valid ? sacc[kb][v] * scale : NEG_BIG;
-          sacc[kb][v] = sv;
-          tmax = fmaxf(tmax, sv);
+          const unsigned bit = ((kb ? whi : wlo) >> (8 * (v >> 2) + (v & 3))) & 1u;
+          sacc[kb][v] = bit ? sacc[kb][v] : NEG_BIG;
         }
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m, tmax);
-    const float alpha = exp2f(m - m_new);
-    float lsum = 0.f;
+    float tmax = NEG_BIG;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float sv = sacc[kb][v];
-        float p = sv > 0.5f * NEG_BIG ? exp2f(sv - m_new) : 0.f;
-        sacc[kb][v] = p;
-        lsum += p;
-      }
-    l = l * alpha + lsum;
+      for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][v]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m, tmax);
+    const float mb = m_new * scale;
+    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0ull) {   // rescale only when some column's max moved
+      const float alpha = __builtin_amdgcn_exp2f(m * scale - mb);
+      l *= alpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
+    }
     m = m_new;
+    float lsum = 0.f;
+    if (masked_tile) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
+        for (int v = 0; v < 16; ++v) {
+          float sv = sacc[kb][v];
+          float p = sv > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(fmaf(sv, scale, -mb)) : 0.f;
+          sacc[kb][v] = p;
+          lsum += p;
+        }
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], scale, -mb));
+          sacc[kb][v] = p;
+          lsum += p;
+        }
+    }
+    l += lsum;
 
     // O^T += V^T P^T: k-step (kb, u) takes registers 8u..8u+7 of block kb, i.e. keys
-    // kb*32 + 16u + {0, 8} + 4*lg + 0..3
-    const unsigned char* vbase = vs + buf * V_TILE_BYTES + lr * V_ROW + 8 * lg;
+    // kb*32 + 16u + {0, 8} + 4*lg + 0..3 -- one 16-byte read in the permuted LDS order
+    const unsigned char* vbase = vs + buf * V_TILE_BYTES + lane * 16;   // fragment (kb, db, u) at (kb*8 + db*2 + u) KB
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int db = 0; db < 4; ++db) fr[0][db] = *reinterpret_cast<const bf16x8_t*>(vbase + db * 2048);
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        bf16x8_t pf;
+    for (int ku = 0; ku < 4; ++ku) {   // k-step ku = 2*kb + u
+      if (ku < 3) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)sacc[kb][8 * u + j];
-        const int koff = 2 * (kb * 32 + 16 * u);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const unsigned char* vptr = vbase + db * 32 * V_ROW + koff;
-          uint2 lo = *reinterpret_cast<const uint2*>(vptr);
-          uint2 hi = *reinterpret_cast<const uint2*>(vptr + 16);
-          uint4 packed = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          bf16x8_t vf = __builtin_bit_cast(bf16x8_t, packed);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
-        }
+        for (int db = 0; db < 4; ++db)
+          fr[(ku + 1) & 1][db] =
+              *reinterpret_cast<const bf16x8_t*>(vbase + (((ku + 1) >> 1) * 8 + db * 2 + ((ku + 1) & 1)) * 1024);
       }
+      bf16x8_t pf;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)sacc[ku >> 1][8 * (ku & 1) + j];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ku & 1][db], pf, oacc[db], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (more)
       attn_store_tile<W>(ks + (buf ^ 1) * K_TILE_BYTES, vs + (buf ^ 1) * V_TILE_BYTES, tid, total - (t + 1) * 64, kreg,
@@ -337,33 +374,49 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
         f32x4_t o4 = {oacc[db][4 * vq], oacc[db][4 * vq + 1], oacc[db][4 * vq + 2], oacc[db][4 * vq + 3]};
         *reinterpret_cast<f32x4_t*>(part_o + item * HD + db * 32 + 8 * vq + 4 * lg) = o4;
       }
-    if (lg == 0) { part_ml[item * 2] = m; part_ml[item * 2 + 1] = l; }
+    if (lg == 0) { part_ml[item * 2] = m * scale; part_ml[item * 2 + 1] = l; }   // m in the exponent's units
   }
 }
 
 // --------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void store4(float* dst, f32x4_t v) { *reinterpret_cast<f32x4_t*>(dst) = v; }
+__device__ __forceinline__ void store4(bf16_t* dst, f32x4_t v) {
+  bf16x4_t o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+  *reinterpret_cast<bf16x4_t*>(dst) = o;
+}
+
+// Merge of the per-split partials, in split order.  hd/4 threads per (row, head) item, four
+// features each; a 256-thread workgroup takes 256/(hd/4) items.
 template <typename T>
-__global__ void k_attn_merge(BlockDev b, KvDev kv, int hq, int hd, const float* __restrict__ part_o,
-                             const float* __restrict__ part_ml, int nsplit, T* __restrict__ out) {
-  const int row = blockIdx.x / hq, h = blockIdx.x % hq;
+__global__ __launch_bounds__(256) void k_attn_merge(BlockDev b, KvDev kv, int hq, int hd,
+                                                    const float* __restrict__ part_o,
+                                                    const float* __restrict__ part_ml, int nsplit,
+                                                    T* __restrict__ out, int n_items) {
+  const int per = hd >> 2;
+  const int item = blockIdx.x * (256 / per) + threadIdx.x / per;   // row * hq + h
+  const int d = (threadIdx.x % per) * 4;
+  if (item >= n_items) return;
+  const int row = item / hq;
   const int seq = row / b.rows_per_seq, r = row % b.rows_per_seq;
   const int nr = b.n_rows[seq];
-  const int d = threadIdx.x;
-  T* dst = out + ((size_t)row * hq + h) * hd + d;
+  T* dst = out + (size_t)item * hd + d;
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
   if (!seq_ok(kv, seq, nr, b.rows_per_seq) || r >= nr) {
-    *dst = from_f32<T>(0.f);
+    store4(dst, acc);
     return;
   }
-  const size_t item0 = ((size_t)row * hq + h) * nsplit;
+  const size_t item0 = (size_t)item * nsplit;
   float mx = NEG_BIG;
   for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, part_ml[(item0 + s) * 2]);
-  float lt = 0.f, acc = 0.f;
+  float lt = 0.f;
   for (int s = 0; s < nsplit; ++s) {
-    float w = exp2f(part_ml[(item0 + s) * 2] - mx);
+    const float w = exp2f(part_ml[(item0 + s) * 2] - mx);
     lt += part_ml[(item0 + s) * 2 + 1] * w;
-    acc += part_o[(item0 + s) * hd + d] * w;
+    const f32x4_t o = *reinterpret_cast<const f32x4_t*>(part_o + (item0 + s) * hd + d);
+    acc += o * w;
   }
-  *dst = from_f32<T>(lt > 0.f ? acc / lt : 0.f);
+  const float inv = lt > 0.f ? 1.f / lt : 0.f;
+  store4(dst, acc * inv);
 }
 
 }  // namespace
@@ -398,9 +451,9 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
     const int G = hq / hkv;
     const int cols = b.rows_per_seq * G;
     const int wave_tiles = (cols + 31) / 32;
-    // waves per workgroup: the count in 2..4 that pads the column range least (ties: larger)
+    // waves per workgroup: 3 or 4, whichever pads the column range less (ties: 4)
     int W = 4, best_pad = 1 << 30;
-    for (int w = 4; w >= 2; --w) {
+    for (int w = 4; w >= 3; --w) {
       int pad = ((wave_tiles + w - 1) / w) * w - wave_tiles;
       if (pad < best_pad) { best_pad = pad; W = w; }
     }
@@ -408,29 +461,13 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
     const int total_wg = q_tiles * hkv * b.batch * p.nsplit;
     dim3 grid(((total_wg + 7) / 8) * 8);
     size_t lds = 2 * (size_t)(K_TILE_BYTES + V_TILE_BYTES);
-    // more than 64 KB of dynamic LDS must be granted per kernel once
-    static bool lds_granted = false;
-    if (!lds_granted) {
-      hipError_t e1 = hipSuccess;
-      hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<2>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<3>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      hipError_t e4 = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<4>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e1 != hipSuccess) return e1;
-      if (e2 != hipSuccess) return e2;
-      if (e3 != hipSuccess) return e3;
-      if (e4 != hipSuccess) return e4;
-      lds_granted = true;
-    }
+    // 64 KB of dynamic LDS: the default limit, no attribute needed
 #define ESP_ATTN_CASE(w)                                                                                  \
   case w:                                                                                                 \
     hipLaunchKernelGGL(k_attn_mfma<w>, grid, dim3(64 * w), lds, st, b, kv, layer, hq, hkv, (const bf16_t*)q, \
                        part_o, part_ml, p.nsplit, p.tiles_per_split, q_tiles);                            \
     break;
     switch (W) {
-      ESP_ATTN_CASE(2)
       ESP_ATTN_CASE(3)
       ESP_ATTN_CASE(4)
     }
@@ -457,11 +494,13 @@ hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const
   const int M = b.batch * b.rows_per_seq;
   const float* part_o = partials;
   const float* part_ml = partials + (size_t)M * hq * p.nsplit * hd;
+  const int n_items = M * hq, per_wg = 256 / (hd / 4);
+  const dim3 grid((n_items + per_wg - 1) / per_wg);
   if (dtype == ESP_F32)
-    hipLaunchKernelGGL(k_attn_merge<float>, dim3(M * hq), dim3(hd), 0, st, b, kv, hq, hd, part_o, part_ml, p.nsplit,
-                       (float*)out);
+    hipLaunchKernelGGL(k_attn_merge<float>, grid, dim3(256), 0, st, b, kv, hq, hd, part_o, part_ml, p.nsplit,
+                       (float*)out, n_items);
   else
-    hipLaunchKernelGGL(k_attn_merge<bf16_t>, dim3(M * hq), dim3(hd), 0, st, b, kv, hq, hd, part_o, part_ml,
-                       p.nsplit, (bf16_t*)out);
+    hipLaunchKernelGGL(k_attn_merge<bf16_t>, grid, dim3(256), 0, st, b, kv, hq, hd, part_o, part_ml, p.nsplit,
+                       (bf16_t*)out, n_items);
   return hipGetLastError();
 }

@@ -24,7 +24,6 @@
 
 namespace {
 
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int KC = 64;            // k per chunk
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
@@ -33,7 +32,7 @@ template <int MT, int NB, int D, bool TILED, int WM, bool AMAX>   // D even; WM 
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
-                                               int m_tiles, int n_tiles) {
+                                               int m_tiles, int n_tiles, int a_ld) {
   // XCD-aware logical id: consecutive hardware ids go to different XCDs, so give each XCD a
   // contiguous range of tiles (tiles sharing weight rows then share an L2).
   const int total = m_tiles * n_tiles * splits;
@@ -80,9 +79,13 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
     int r = p >> 3, c16 = p & 7;
     int m = min(mt0 + r, M - 1);
     if (a_rows) m = max(a_rows[m], 0);
-    ap[i] = A + (size_t)m * K + c16 * 8;
+    ap[i] = A + (a_ld > 0 ? (size_t)m * KC : (size_t)m * K) + c16 * 8;
     a_lds[i] = r * A_ROW_BYTES + c16 * 16;
   }
+  // activations: row-major [M][K] (a_ld == 0), or chunk-major [K/64][a_ld][64] where the rows of
+  // one 64-wide k chunk are contiguous (row-major puts them 2K bytes apart, which lands every row
+  // of a chunk on the same L2 channel when all workgroups walk the chunks in step)
+  const size_t a_cs = a_ld > 0 ? (size_t)a_ld * KC : (size_t)KC;
   constexpr int A_BUF = WM * MT * 32 * A_ROW_BYTES;
 
   f32x16_t acc[MT][NB];
@@ -107,7 +110,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
     const int c = c_begin + u;
     const int cc = min(c, c_last);
 #pragma unroll
-    for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * KC);
+    for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * a_cs);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -155,7 +158,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         const int cn = c + D;
         const int cc = min(cn, c_last);
 #pragma unroll
-        for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * KC);
+        for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * a_cs);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -238,17 +241,17 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
 template <int MT, int NB, int D, bool TILED, bool AMAX>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
-                                                   int N, int K, int splits, int m_tiles, int n_tiles) {
+                                                   int N, int K, int splits, int m_tiles, int n_tiles, int a_ld) {
   extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
-  gemm_bf16_body<MT, NB, D, TILED, 1, AMAX>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+  gemm_bf16_body<MT, NB, D, TILED, 1, AMAX>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
 }
 
 template <int MT, int NB, int D, bool TILED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_big(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
-    float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles) {
+    float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_bf16_body<MT, NB, D, TILED, 1, false>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles);
+  gemm_bf16_body<MT, NB, D, TILED, 1, false>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -315,16 +318,17 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
 
 template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), bool AMAX = false>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
-                       int N, int K, const GemmPlan& p) {
+                       int N, int K, const GemmPlan& p, int a_ld = 0) {
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
-  if (MT * NB >= 8)
+  if constexpr (MT * NB >= 8)
     hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st,
-                       (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
+                       (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles,
+                       a_ld);
   else
     hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, AMAX>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
-                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles);
+                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld);
   return hipGetLastError();
 }
 
@@ -402,14 +406,14 @@ bool gemm_argmax_supported(int dtype, int M, int N, int K) {
 size_t gemm_argmax_scratch_floats(int M, int N) { return (size_t)((N + 127) / 128) * M * 2; }
 
 hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
-                              int K, float* scratch, int32_t* out, const int32_t* out_index) {
+                              int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld) {
   GemmPlan p = gemm_plan(ESP_BF16, M, N, K);
   hipError_t e = hipErrorInvalidValue;
   switch (p.mt) {
-    case 1: e = launch_bf16<1, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
-    case 2: e = launch_bf16<2, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
-    case 3: e = launch_bf16<3, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
-    case 4: e = launch_bf16<4, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p); break;
+    case 1: e = launch_bf16<1, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 2: e = launch_bf16<2, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 3: e = launch_bf16<3, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 4: e = launch_bf16<4, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
   }
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_argmax_tiles, dim3(M), dim3(256), 0, st, scratch, p.n_tiles, M, out, out_index);
@@ -424,7 +428,7 @@ hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N,
 }
 
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
-                       float* out, int M, int N, int K, const GemmPlan& p, bool w_packed) {
+                       float* out, int M, int N, int K, const GemmPlan& p, bool w_packed, int a_ld) {
   if (M <= 0) return hipSuccess;
   if (dtype == ESP_F32) {
     hipLaunchKernelGGL(k_gemm_f32, dim3(p.n_tiles, p.m_tiles), dim3(256), 0, st, (const float*)A, a_rows,
@@ -433,8 +437,8 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* 
   }
 #define ESP_GEMM_CASE(MT_, NB_)                                                                  \
   if (p.mt == MT_ && p.nb == NB_)                                                                \
-    return w_packed ? launch_bf16<MT_, NB_, true>(st, A, a_rows, W, out, M, N, K, p)             \
-                    : launch_bf16<MT_, NB_, false>(st, A, a_rows, W, out, M, N, K, p);
+    return w_packed ? launch_bf16<MT_, NB_, true>(st, A, a_rows, W, out, M, N, K, p, a_ld)       \
+                    : launch_bf16<MT_, NB_, false>(st, A, a_rows, W, out, M, N, K, p, a_ld);
   ESP_GEMM_CASE(1, 1)
   ESP_GEMM_CASE(2, 1)
   ESP_GEMM_CASE(3, 1)

@@ -12,6 +12,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));   // 16 raw bytes in registers
 
 #define ESP_WAVE 64
 
@@ -34,15 +35,23 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- KV cache addressing (see esp_kv in esp.h) --------------------------------------------
-// K: [layer][kv_head][capacity][hd]; V: [layer][kv_head][capacity/64][hd][64]
+// Per (layer, kv head) plane of capacity*hd elements, in blocks of 32 slots stored in the order
+// the matrix cores consume them (v_mfma_f32_32x32x16 A operands, 64 lanes x 8 elements each):
+//   K block: [hd/16 k-steps][64 lanes][8]   lane (slot%32, half) holds features 16*step + 8*half + 0..7
+//            (A operand of S^T = K Q^T: row = key, contraction over features)
+//   V block: [hd/32 feature blocks][2 key-steps][64 lanes][8]   lane (feature%32, half), element j
+//            holds key 16*step + 8*(j/4) + 4*half + j%4 -- the order in which the S^T accumulator
+//            registers of a lane half line up as B operand of O^T = V^T P^T
+// so a tile of keys is one contiguous run of bytes and every fragment is one 16-byte load per lane.
 __host__ __device__ __forceinline__ size_t kv_plane(int layer, int kvh, int n_kv, int64_t cap, int hd) {
   return ((size_t)layer * n_kv + kvh) * (size_t)cap * hd;
 }
 __host__ __device__ __forceinline__ size_t k_off(int64_t slot, int d, int hd) {
-  return (size_t)slot * hd + d;
+  return (size_t)(slot >> 5) * hd * 32 + (size_t)((((d >> 4) * 64 + ((d >> 3) & 1) * 32 + (int)(slot & 31)) << 3) + (d & 7));
 }
 __host__ __device__ __forceinline__ size_t v_off(int64_t slot, int d, int hd) {
-  return ((size_t)(slot >> 6) * hd + d) * 64 + (slot & 63);
+  const int key = (int)(slot & 31), u = key >> 4, half = (key >> 2) & 1, j = ((key >> 3) & 1) * 4 + (key & 3);
+  return (size_t)(slot >> 5) * hd * 32 + (size_t)(((((d >> 5) * 2 + u) * 64 + half * 32 + (d & 31)) << 3) + j);
 }
 
 // ---- GEMM -----------------------------------------------------------------------------------
@@ -59,13 +68,14 @@ inline size_t gemm_out_elems(const GemmPlan& p, int M, int N) { return (size_t)p
 // out: fp32 [splits][M][N].  a_rows (device, may be null): physical row of A for logical row m.
 // w_packed: W is in the streaming layout written by launch_pack_weight (bf16 only).
 hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* a_rows, const void* W,
-                       float* out, int M, int N, int K, const GemmPlan& p, bool w_packed);
+                       float* out, int M, int N, int K, const GemmPlan& p, bool w_packed, int a_ld = 0);
+// a_ld == 0: A is row-major [rows][K]; a_ld > 0 (bf16 only): A is chunk-major [K/64][a_ld][64]
 hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K);
 // LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows, one split)
 bool gemm_argmax_supported(int dtype, int M, int N, int K);
 size_t gemm_argmax_scratch_floats(int M, int N);
 hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
-                              int K, float* scratch, int32_t* out, const int32_t* out_index);
+                              int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld = 0);
 
 // ---- elementwise / glue (esp_elementwise.hip) ----------------------------------------------
 struct BlockDev {   // device-side view of esp_block + esp_kv scalars, passed by value
