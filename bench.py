@@ -35,6 +35,26 @@ def gemm_algorithmic_bytes(M, N, K):
     return 2 * N * K + 2 * M * K + 4 * M * N
 
 
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "esp_step_llama3_8b_kv2048_hbm_traffic_pmc.txt")
+
+
+def measured_traffic(layout, rows):
+    """HBM bytes per launch of the layer-projection GEMM, averaged over its four launches per
+    layer, from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, both scaled by
+    a copy kernel of known size; the summary states the commands and the scale).  None when the
+    summary has no line for this layout and row count."""
+    try:
+        for line in open(PMC_SUMMARY):
+            if not line.startswith("bench-traffic "):
+                continue
+            kv = dict(f.split("=", 1) for f in line.split()[1:])
+            if kv.get("layout") == layout and int(kv.get("rows", -1)) == rows:
+                return float(kv["hbm_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
+
+
 def run_config(B, decode, synth, torch, shape, weights, eng_holder, layout, n_nodes, k, K, kp, L, steps, warmup,
                prompt, profile_every=4):
     params = B.tree_params(n_nodes, k, K, 0, True, False, layout)
@@ -180,7 +200,7 @@ def main():
         alt_r = run_config(B, decode, synth, torch, shape, weights, holder, layouts[alt_name], n_nodes, k, K, kp, L,
                            args.steps, args.warmup, prompt)
 
-    def summarise(r):
+    def summarise(r, layout_name):
         rows = r["rows"]
         tokens_per_s = r["emitted"] / (r["ms_per_step"] * args.steps / 1e3)
         shapes = layer_gemm_shapes(shape)
@@ -197,7 +217,8 @@ def main():
                     tau=r["emitted"] / args.steps,
                     roofline={"kernel": "k_gemm_bf16 (layer projections: QKV, O, gate/up, down)", "bound": "hbm",
                               "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
+                              "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                              "traffic": measured_traffic(layout_name, rows),
                               "bytes_per_launch": per_launch, "avg_launch_ms": avg_ms, "launches_timed": r["n_spans"],
                               "mfma_tflops": flops / (avg_ms * 1e-3) / 1e12 if r["n_spans"] else None},
                     roofline_attn={"kernel": "k_attn_mfma", "bound": "hbm",
@@ -206,7 +227,7 @@ def main():
                                    "avg_launch_ms": attn_ms, "kv_len": Lnow},
                     breakdown_ms_per_step={s: round(v["ms_per_step"], 4) for s, v in r["breakdown"].items()})
 
-    sm = summarise(main_r)
+    sm = summarise(main_r, args.layout)
     weight_bytes = shape.n_layers * sum(2 * N * Kd for N, Kd in layer_gemm_shapes(shape)) + \
         2 * 2 * shape.vocab * shape.d_model
     out = {
@@ -224,7 +245,7 @@ def main():
         "setup_s": round(t_setup, 1),
     }
     if alt_r is not None:
-        sa = summarise(alt_r)
+        sa = summarise(alt_r, alt_name)
         out["alt_layout"] = {"layout": alt_name, "rows_per_step": sa["rows"], "tokens_per_s": sa["tokens_per_s"],
                              "ms_per_step": sa["ms_per_step"], "roofline": sa["roofline"],
                              "roofline_attn": sa["roofline_attn"],

@@ -119,20 +119,18 @@ __device__ __forceinline__ void attn_load_tile(const bf16_t* __restrict__ kt, co
   }
 }
 
-// keys_left: keys of the tile that belong to the sequence; V of the others is zeroed (their
-// probability is zero, but 0 * NaN from never-written cache memory would poison the MFMA)
-template <int W>
-__device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char* vs, int tid, int keys_left,
-                                                const u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
-                                                const u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
+template <int W, bool LAST>
+__device__ __forceinline__ void attn_store_pieces(unsigned char* ks, unsigned char* vs, int tid, int keys_left,
+                                                  const u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
+                                                  const u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
   constexpr int NT = 64 * W, PIECES = (1024 + NT - 1) / NT;
 #pragma unroll
   for (int i = 0; i < PIECES; ++i) {
     int p = tid + NT * i;
-    if (p < 1024) {
+    if (1024 % NT == 0 || p < 1024) {
       *reinterpret_cast<u32x4_t*>(ks + p * 16) = kreg[i];
       u32x4_t v = vreg[i];
-      if (keys_left < 64) {                     // last tile of the sequence only (uniform branch)
+      if (LAST) {
         // piece p = fragment (block p/512, key-step (p/64)%2) of lane p%64; word w holds elements
         // 2w, 2w+1 = keys k0, k0+1
         const int kbase = (p >> 9) * 32 + ((p >> 6) & 1) * 16 + ((p >> 5) & 1) * 4;
@@ -145,6 +143,17 @@ __device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char
       *reinterpret_cast<u32x4_t*>(vs + p * 16) = v;
     }
   }
+}
+
+// keys_left: keys of the tile that belong to the sequence; V of the others is zeroed (their
+// probability is zero, but 0 * NaN from never-written cache memory would poison the MFMA).
+// Only the last tile of a sequence takes that path (one uniform branch).
+template <int W>
+__device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char* vs, int tid, int keys_left,
+                                                const u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
+                                                const u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
+  if (keys_left < 64) attn_store_pieces<W, true>(ks, vs, tid, keys_left, kreg, vreg);
+  else attn_store_pieces<W, false>(ks, vs, tid, keys_left, kreg, vreg);
 }
 
 // Visibility bits of 64 consecutive keys for one block row: bit j stands for block position
@@ -252,7 +261,10 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
       attn_load_tile<W>(kt0 + (size_t)tn * 64 * HD, vt0 + (size_t)tn * 64 * HD, tid, kreg, vreg);
     }
 
-    // S^T = K Q^T for the two 32-key blocks of the tile
+    // S^T = K Q^T for the two 32-key blocks of the tile.  The MFMA phases run at raised wave
+    // priority: of the two waves that share a SIMD, the one with matrix work issues first and the
+    // other fills the gaps with its softmax arithmetic.
+    __builtin_amdgcn_s_setprio(2);
     f32x16_t sacc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -296,6 +308,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
           sacc[kb][v] = bit ? sacc[kb][v] : NEG_BIG;
         }
     }
+    __builtin_amdgcn_s_setprio(0);
     float tmax = NEG_BIG;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -338,6 +351,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
 
     // O^T += V^T P^T: k-step (kb, u) takes registers 8u..8u+7 of block kb, i.e. keys
     // kb*32 + 16u + {0, 8} + 4*lg + 0..3 -- one 16-byte read in the permuted LDS order
+    __builtin_amdgcn_s_setprio(2);
     const unsigned char* vbase = vs + buf * V_TILE_BYTES + lane * 16;   // fragment (kb, db, u) at (kb*8 + db*2 + u) KB
 #pragma unroll
     for (int db = 0; db < 4; ++db) fr[0][db] = *reinterpret_cast<const bf16x8_t*>(vbase + db * 2048);
@@ -358,6 +372,7 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ku & 1][db], pf, oacc[db], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_setprio(0);
     if (more)
       attn_store_tile<W>(ks + (buf ^ 1) * K_TILE_BYTES, vs + (buf ^ 1) * V_TILE_BYTES, tid, total - (t + 1) * 64, kreg,
                          vreg);
