@@ -139,6 +139,86 @@ def cpu_baseline(torch, synth, shape, weights, n_nodes, k, K, kp, L, layout):
                       f"extrapolated as {shape.n_layers} x layer + rest = {t_step:.1f} s"}
 
 
+def time_gpu(torch, fn, iters, warm=2):
+    """Mean ms per call of fn, timed with events on the stream the library launches on."""
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def stage_rooflines(B, synth, torch, shape, lm_head_packed):
+    """Stage-level figures for the pieces whose roofline the step workload cannot show: tree
+    attention at a 32768-token cache (one layer, rotating over 4 layers of KV so the reads come
+    from HBM), the LM-head GEMM at a batched-verification row count (MFMA-bound), and the fused
+    softmax + Top-K' over many logit rows."""
+    out = {}
+    L, nl = 32768, 4
+    sh = shape.replace(n_layers=nl, vocab=1024, d_ff=256)
+    w = synth.make_weights(sh, seed=1, device="cuda")
+    eng = B.Engine(sh, w, 1, 320, L + 1024)
+    kv = B.KvCache(sh, [L + 512])
+    kf, vf = synth.make_kv_fill(sh.replace(n_layers=1), L + 320, seed=5, device="cuda")
+    for l in range(nl):
+        eng.kv_store(kv, l, 0, 0, kf[0].contiguous(), vf[0].contiguous())
+    kv.set_len([L])
+    for layout, rows in [(B.LAYOUT_ROOT_CHAIN, 68), (B.LAYOUT_PER_NODE, 320)]:
+        tok, par = synth.make_random_tree(64, 4, sh.vocab, seed=9)
+        blk = B.BlockBuffers(1, rows, 4, layout)
+        blk.upload_trees([tok.tolist()], [par.tolist()])
+        eng.block_from_tree(blk)
+        q = synth.normal_like((rows, sh.n_q_heads, sh.head_dim), 1.0, 3, layout, "cuda", torch.bfloat16)
+        o = torch.zeros_like(q)
+        cnt = [0]
+
+        def call():
+            eng.attn_tree(blk, kv, cnt[0] % nl, q, o)
+            cnt[0] += 1
+        ms = time_gpu(torch, call, 20, warm=3)
+        byts = (L + rows) * sh.n_kv_heads * sh.head_dim * 2 * 2 + 2 * rows * sh.n_q_heads * sh.head_dim * 2
+        flops = 4.0 * rows * sh.n_q_heads * sh.head_dim * (L + rows)
+        out[f"attn_L32768_rows{rows}"] = {
+            "kernel": "k_attn_mfma + k_attn_merge", "bound": "hbm", "achieved": byts / ms / 1e6, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": byts / ms / 1e6 / HBM_PEAK_GBS, "bytes_per_launch": byts, "avg_launch_ms": ms,
+            "mfma_tflops": flops / ms / 1e9}
+    assert eng.device_status() == 0
+    eng.close()
+    del eng, kv, kf, vf, w
+    torch.cuda.empty_cache()
+
+    M, N, K = 1344, shape.vocab, shape.d_model           # 16 sequences x (80 + 4) rows
+    A = synth.normal_like((M, K), 1.0, 21, 0, "cuda", torch.bfloat16)
+    C_out = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    scratch = torch.empty(max(B.load_library().esp_gemm_scratch_bytes(M, N, K), 256), dtype=torch.uint8, device="cuda")
+    ms = time_gpu(torch, lambda: B.gemm(A, lm_head_packed, True, C_out, scratch), 5, warm=2)
+    fl = 2.0 * M * N * K
+    out["lm_head_rows1344"] = {"kernel": "k_gemm_bf16 (LM head, 1344 rows)", "bound": "mfma", "achieved": fl / ms / 1e9,
+                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                               "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": ms}
+    del A, scratch
+    for rows in (4, 256, 1344):
+        lg = C_out[:rows]
+        bufs = (torch.empty((rows, 10), dtype=torch.int32, device="cuda"),
+                torch.empty((rows, 10), dtype=torch.float32, device="cuda"),
+                torch.empty(max(B.load_library().esp_softmax_topk_scratch_bytes(rows, N, 10), 256), dtype=torch.uint8,
+                            device="cuda"))
+        ms = time_gpu(torch, lambda: B.softmax_topk(lg, 10, bufs), 10, warm=2)
+        byts = rows * N * 4
+        out[f"softmax_topk_rows{rows}"] = {"kernel": "k_topk_chunks + k_topk_merge", "bound": "hbm",
+                                           "achieved": byts / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                           "frac": byts / ms / 1e6 / HBM_PEAK_GBS, "bytes_per_launch": byts,
+                                           "avg_launch_ms": ms}
+    del C_out
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -148,6 +228,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-alt", action="store_true", help="skip the second layout")
     ap.add_argument("--kv-len", type=int, default=2048)
+    ap.add_argument("--no-stages", action="store_true", help="skip the stage-level roofline figures")
     ap.add_argument("--fast-weights", action="store_true",
                     help="draw the weights with torch.Tensor.normal_ (one kernel per tensor) instead of the "
                          "counter-based generator; for counter-collection runs, where tens of thousands of "
@@ -250,6 +331,8 @@ def main():
                              "ms_per_step": sa["ms_per_step"], "roofline": sa["roofline"],
                              "roofline_attn": sa["roofline_attn"],
                              "breakdown_ms_per_step": sa["breakdown_ms_per_step"]}
+    if not args.no_stages:
+        out["stage_rooflines"] = stage_rooflines(B, synth, torch, shape, holder["eng"].lm_head)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, shape, weights, n_nodes, k, K, kp, L,
                                            layouts[args.layout])

@@ -377,27 +377,38 @@ def pack_weight(w: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def gemm(A: torch.Tensor, W: torch.Tensor, packed: bool = False) -> torch.Tensor:
-    """out[M,N] fp32 = A[M,K] @ W[N,K]^T through esp_gemm (W row-major, or packed by pack_weight)."""
+def gemm(A: torch.Tensor, W: torch.Tensor, packed: bool = False, out: Optional[torch.Tensor] = None,
+         scratch: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[M,N] fp32 = A[M,K] @ W[N,K]^T through esp_gemm (W row-major, or packed by pack_weight).
+    out / scratch (uint8, esp_gemm_scratch_bytes) may be passed in to keep allocation out of a loop."""
     lib = load_library()
     M, K = A.shape
     N = W.shape[0]
     code = ESP_BF16 if A.dtype == torch.bfloat16 else ESP_F32
-    out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
     nb = lib.esp_gemm_scratch_bytes(M, N, K)
-    scratch = torch.empty(max(nb, 256), dtype=torch.uint8, device=A.device)
+    if scratch is None:
+        scratch = torch.empty(max(nb, 256), dtype=torch.uint8, device=A.device)
+    assert scratch.numel() >= nb and out.shape == (M, N) and out.dtype == torch.float32
     _check(lib.esp_gemm(_stream_ptr(), code, _ptr(A), _ptr(W), int(packed), _ptr(out), M, N, K, _ptr(scratch),
                         nb), "esp_gemm")
     return out
 
 
-def softmax_topk(logits: torch.Tensor, kp: int):
+def softmax_topk(logits: torch.Tensor, kp: int, bufs=None):
+    """(ids, probs) of the kp largest softmax probabilities per row; bufs = (ids, probs, scratch)
+    may be passed in to keep allocation out of a loop."""
     lib = load_library()
     rows, vocab = logits.shape
-    ids = torch.empty((rows, kp), dtype=torch.int32, device=logits.device)
-    ps = torch.empty((rows, kp), dtype=torch.float32, device=logits.device)
     nb = lib.esp_softmax_topk_scratch_bytes(rows, vocab, kp)
-    scratch = torch.empty(max(nb, 256), dtype=torch.uint8, device=logits.device)
+    if bufs is None:
+        ids = torch.empty((rows, kp), dtype=torch.int32, device=logits.device)
+        ps = torch.empty((rows, kp), dtype=torch.float32, device=logits.device)
+        scratch = torch.empty(max(nb, 256), dtype=torch.uint8, device=logits.device)
+    else:
+        ids, ps, scratch = bufs
+        assert scratch.numel() >= nb
     _check(lib.esp_softmax_topk(_stream_ptr(), _ptr(logits), rows, vocab, kp, _ptr(ids), _ptr(ps), _ptr(scratch),
                                 nb), "esp_softmax_topk")
     return ids, ps

@@ -1,159 +1,241 @@
 // Fused vocabulary softmax + Top-K' of the mask-row logits (paper Sec. 2 Eq. 2, Sec. 3.3).
 //
-// Each logit row is read exactly once.  Pass 1: a workgroup takes a chunk of 2048 logits of one
-// row into registers, reduces the chunk maximum and sum of exponentials (wavefront shuffles, then
-// LDS across the four waves) and extracts the chunk's K' largest (value desc, id asc) by K' rounds
-// of block arg-max.  Pass 2: one workgroup per row merges the chunk statistics (online-softmax
-// rule) and selects the K' best of the chunk winners from LDS; p = exp(v - max) / sum in fp32.
+// Each logit row is read exactly once, by independent wavefronts and without a barrier.
+// Pass 1 (k_topk_stream): a wave streams one segment of one row in blocks of 2048 logits
+// (32 per lane, float4 loads, the next block in flight while the current one is reduced).
+//   * softmax statistics stay lane-local (running maximum and rescaled sum of exponentials) and
+//     are combined across the wave once, at the end of the segment;
+//   * the K' best (value desc, id asc) live in a list spread over the lanes (lane j holds the
+//     j-th best).  A block is only looked at when its maximum reaches the current K'-th value,
+//     which after the first block is rare (about K' ln(n/K') times per n logits), so the common
+//     path per logit is one max, one fma, one exp and one add.  The first block is filtered by the
+//     K'-th largest of its 64 lane maxima (at least K' logits reach that bound), which keeps the
+//     warm-up to a few insertions.
+// Pass 2 (k_topk_merge): one wave per row merges the segment statistics (online-softmax rule) and
+// runs the same filtered insertion over the segments' candidates; p = exp(v - max) / sum in fp32.
+#include <algorithm>
+
 #include "esp_internal.h"
 
 namespace {
 
-constexpr int CHUNK = 2048;
-constexpr int PER_THREAD = CHUNK / 256;
+constexpr int BLOCK = 2048;            // logits per wave and iteration
+constexpr int PER_LANE = BLOCK / 64;
+constexpr float LOG2E_F = 1.4426950408889634f;
 
-struct Best {
-  float v;
-  int id;
-};
 __device__ __forceinline__ bool better(float av, int ai, float bv, int bi) {
   return av > bv || (av == bv && ai < bi);
 }
-__device__ __forceinline__ Best wave_best(Best b) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(b.v, o, 64);
-    int oi = __shfl_xor(b.id, o, 64);
-    if (better(ov, oi, b.v, b.id)) { b.v = ov; b.id = oi; }
-  }
-  return b;
-}
-// all threads get the block-wide best; sv/si are 4-entry LDS arrays
-__device__ __forceinline__ Best block_best(Best b, float* sv, int* si) {
-  b = wave_best(b);
-  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = b.v; si[threadIdx.x >> 6] = b.id; }
-  __syncthreads();
-  Best r = {sv[0], si[0]};
-#pragma unroll
-  for (int w = 1; w < 4; ++w)
-    if (better(sv[w], si[w], r.v, r.id)) { r.v = sv[w]; r.id = si[w]; }
-  __syncthreads();
-  return r;
+__device__ __forceinline__ float readlane_f(float v, int l) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
 
-// scratch per (row, chunk): [max, sum, v_0..v_{kp-1}, id_0..id_{kp-1}] as 2 + 2*kp words
-__global__ __launch_bounds__(256) void k_topk_chunks(const float* __restrict__ logits, int vocab, int kp,
-                                                     int nchunks, float* __restrict__ scratch) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
-  const int row = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
+// The K' best so far, lane j < kp holding the j-th; lanes >= kp hold (-inf, INT_MAX).
+struct LaneList {
+  float v;
+  int id;
+  float last_v;   // entry kp-1 (wave-uniform)
+  int last_id;
+};
+__device__ __forceinline__ void list_init(LaneList& L) {
+  L.v = -INFINITY; L.id = 0x7fffffff; L.last_v = -INFINITY; L.last_id = 0x7fffffff;
+}
+// insert (v, id), known to be better than the last entry; v, id wave-uniform
+__device__ __forceinline__ void list_insert(LaneList& L, float v, int id, int kp, int lane) {
+  const bool mine_better = lane < kp && better(L.v, L.id, v, id);
+  const int pos = __popcll(__builtin_amdgcn_ballot_w64(mine_better));   // the better entries form a prefix
+  const float up_v = __shfl_up(L.v, 1, 64);
+  const int up_i = __shfl_up(L.id, 1, 64);
+  if (lane < kp) {
+    if (lane == pos) { L.v = v; L.id = id; }
+    else if (lane > pos) { L.v = up_v; L.id = up_i; }
+  }
+  L.last_v = readlane_f(L.v, kp - 1);
+  L.last_id = __builtin_amdgcn_readlane(L.id, kp - 1);
+}
+
+// kp-th largest of the 64 lane values (bitonic sort across the wave, descending); kp <= 64
+__device__ __forceinline__ float kth_largest_lane(float x, int kp, int lane) {
+#pragma unroll
+  for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      const float o = __shfl_xor(x, j, 64);
+      const bool desc = (lane & k) == 0;            // direction of this lane's subsequence
+      const bool low = (lane & j) == 0;             // lower index of the pair
+      const float hi = fmaxf(x, o), lo = fminf(x, o);
+      x = (desc == low) ? hi : lo;
+    }
+  }
+  return readlane_f(x, kp - 1);
+}
+
+// Offer the values of one register slot (one per lane) to the list: every lane whose value
+// reaches the bound is examined in turn (wave-uniform loop over the ballot).
+__device__ __forceinline__ void offer(LaneList& L, float v, int my_id, float& bound, float floor_bound, int kp,
+                                      int lane) {
+  unsigned long long mask = __builtin_amdgcn_ballot_w64(v >= bound);
+  while (mask) {
+    const int l = __builtin_ctzll(mask);
+    mask &= mask - 1;
+    const float cv = readlane_f(v, l);
+    const int cid = __builtin_amdgcn_readlane(my_id, l);
+    if (better(cv, cid, L.last_v, L.last_id)) {
+      list_insert(L, cv, cid, kp, lane);
+      bound = fmaxf(floor_bound, L.last_v);
+      mask &= __builtin_amdgcn_ballot_w64(v >= bound);
+    }
+  }
+}
+
+// scratch per (row, segment): [max, sum, v_0..v_{kp-1}, id_0..id_{kp-1}] as 2 + 2*kp words
+__global__ __launch_bounds__(256) void k_topk_stream(const float* __restrict__ logits, int rows, int vocab, int kp,
+                                                     int nseg, int seg_len, float* __restrict__ scratch) {
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= rows * nseg) return;
+  const int row = item / nseg, seg = item % nseg;
+  const int start = seg * seg_len, end = min(vocab, start + seg_len);
   const float* p = logits + (size_t)row * vocab;
-  const int c0 = chunk * CHUNK;
-  float v[PER_THREAD];
-  float lmax = -INFINITY;
+  const bool vec4 = (vocab & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
+  const int nblocks = (max(end - start, 0) + BLOCK - 1) / BLOCK;
+
+  // element e of float4 i of the lane sits at block_base + i*256 + lane*4 + e
+  float nxt[PER_LANE], cur[PER_LANE];
+  auto load_block = [&](int b, float (&dst)[PER_LANE]) {
+    const int base = start + b * BLOCK + lane * 4;
+    if (vec4 && start + (b + 1) * BLOCK <= end) {
 #pragma unroll
-  for (int i = 0; i < PER_THREAD; ++i) {
-    int idx = c0 + i * 256 + tid;
-    v[i] = idx < vocab ? p[idx] : -INFINITY;
-    lmax = fmaxf(lmax, v[i]);
+      for (int i = 0; i < PER_LANE / 4; ++i) {
+        const f32x4_t q = *reinterpret_cast<const f32x4_t*>(p + base + i * 256);
+        dst[4 * i] = q[0]; dst[4 * i + 1] = q[1]; dst[4 * i + 2] = q[2]; dst[4 * i + 3] = q[3];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < PER_LANE; ++i) {
+        const int idx = base + (i >> 2) * 256 + (i & 3);
+        dst[i] = idx < end ? p[idx] : -INFINITY;
+      }
+    }
+  };
+
+  LaneList L;
+  list_init(L);
+  float m = -INFINITY, s = 0.f;       // lane-local running maximum and sum of 2^((v - m) log2 e)
+  float floor_bound = -INFINITY, bound = -INFINITY;
+  if (nblocks > 0) load_block(0, nxt);
+  for (int b = 0; b < nblocks; ++b) {
+#pragma unroll
+    for (int i = 0; i < PER_LANE; ++i) cur[i] = nxt[i];
+    if (b + 1 < nblocks) load_block(b + 1, nxt);
+    float bmax = cur[0];
+#pragma unroll
+    for (int i = 1; i < PER_LANE; ++i) bmax = fmaxf(bmax, cur[i]);
+    const float m_new = fmaxf(m, bmax);
+    if (m_new > -INFINITY) {
+      const float mb = m_new * LOG2E_F;
+      float acc = s * __builtin_amdgcn_exp2f(m * LOG2E_F - mb);   // m = -inf: 0
+#pragma unroll
+      for (int i = 0; i < PER_LANE; ++i) acc += __builtin_amdgcn_exp2f(fmaf(cur[i], LOG2E_F, -mb));
+      s = acc;
+      m = m_new;
+    }
+    if (b == 0) {
+      floor_bound = kth_largest_lane(bmax, kp, lane);
+      bound = floor_bound;
+    }
+    if (__builtin_amdgcn_ballot_w64(bmax >= bound) != 0ull) {
+      const int base = start + b * BLOCK + lane * 4;
+#pragma unroll
+      for (int i = 0; i < PER_LANE; ++i) offer(L, cur[i], base + (i >> 2) * 256 + (i & 3), bound, floor_bound, kp, lane);
+    }
   }
-  float cmax = wave_max(lmax);
-  if ((tid & 63) == 0) sv[tid >> 6] = cmax;
-  __syncthreads();
-  cmax = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-  __syncthreads();
-  float lsum = 0.f;
-#pragma unroll
-  for (int i = 0; i < PER_THREAD; ++i) lsum += v[i] == -INFINITY ? 0.f : expf(v[i] - cmax);
-  float csum = wave_sum(lsum);
-  if ((tid & 63) == 0) sv[tid >> 6] = csum;
-  __syncthreads();
-  csum = (sv[0] + sv[1]) + (sv[2] + sv[3]);
-  __syncthreads();
-  float* out = scratch + ((size_t)row * nchunks + chunk) * (2 + 2 * kp);
-  if (tid == 0) { out[0] = cmax; out[1] = csum; }
-  for (int j = 0; j < kp; ++j) {
-    Best mine = {-INFINITY, 0x7fffffff};
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-      int idx = c0 + i * 256 + tid;
-      if (better(v[i], idx, mine.v, mine.id) && v[i] != -INFINITY) { mine.v = v[i]; mine.id = idx; }
-    }
-    Best win = block_best(mine, sv, si);
-    if (tid == 0) {
-      out[2 + j] = win.v;
-      reinterpret_cast<int*>(out)[2 + kp + j] = win.id;
-    }
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i)
-      if (c0 + i * 256 + tid == win.id) v[i] = -INFINITY;
+  // wave-wide statistics in the natural-exponent convention: sum of exp(v - max)
+  const float wm = wave_max(m);
+  const float contrib = m > -INFINITY ? s * __builtin_amdgcn_exp2f((m - wm) * LOG2E_F) : 0.f;
+  const float ws = wave_sum(contrib);
+  float* out = scratch + ((size_t)row * nseg + seg) * (2 + 2 * kp);
+  if (lane == 0) { out[0] = wm; out[1] = ws; }
+  if (lane < kp) {
+    out[2 + lane] = L.v;
+    reinterpret_cast<int*>(out)[2 + kp + lane] = L.id;
   }
 }
 
-__global__ __launch_bounds__(256) void k_topk_merge(const float* __restrict__ scratch, int kp, int nchunks,
+// one wave per row
+__global__ __launch_bounds__(256) void k_topk_merge(const float* __restrict__ scratch, int rows, int kp, int nseg,
                                                     int32_t* __restrict__ ids, float* __restrict__ probs) {
-  extern __shared__ float cand[];     // [nchunks*kp] values then [nchunks*kp] ids
-  __shared__ float sv[4];
-  __shared__ int si[4];
-  const int row = blockIdx.x, tid = threadIdx.x;
-  const int ncand = nchunks * kp;
-  float* cv = cand;
-  int* ci = reinterpret_cast<int*>(cand + ncand);
-  const float* base = scratch + (size_t)row * nchunks * (2 + 2 * kp);
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int stride = 2 + 2 * kp;
+  const float* base = scratch + (size_t)row * nseg * stride;
   float lmax = -INFINITY;
-  for (int c = tid; c < nchunks; c += 256) lmax = fmaxf(lmax, base[(size_t)c * (2 + 2 * kp)]);
-  float gmax = wave_max(lmax);
-  if ((tid & 63) == 0) sv[tid >> 6] = gmax;
-  __syncthreads();
-  gmax = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-  __syncthreads();
+  for (int c = lane; c < nseg; c += 64) lmax = fmaxf(lmax, base[(size_t)c * stride]);
+  const float gmax = wave_max(lmax);
   float lsum = 0.f;
-  for (int c = tid; c < nchunks; c += 256) {
-    const float* e = base + (size_t)c * (2 + 2 * kp);
-    lsum += e[1] * expf(e[0] - gmax);
+  for (int c = lane; c < nseg; c += 64) {
+    const float* e = base + (size_t)c * stride;
+    lsum += e[0] > -INFINITY ? e[1] * expf(e[0] - gmax) : 0.f;
   }
-  float tot = wave_sum(lsum);
-  if ((tid & 63) == 0) sv[tid >> 6] = tot;
-  __syncthreads();
-  tot = (sv[0] + sv[1]) + (sv[2] + sv[3]);
-  __syncthreads();
-  for (int i = tid; i < ncand; i += 256) {
-    const float* e = base + (size_t)(i / kp) * (2 + 2 * kp);
-    cv[i] = e[2 + i % kp];
-    ci[i] = reinterpret_cast<const int*>(e)[2 + kp + i % kp];
-  }
-  __syncthreads();
-  for (int j = 0; j < kp; ++j) {
-    Best mine = {-INFINITY, 0x7fffffff};
-    for (int i = tid; i < ncand; i += 256)
-      if (cv[i] != -INFINITY && better(cv[i], ci[i], mine.v, mine.id)) { mine.v = cv[i]; mine.id = ci[i]; }
-    Best win = block_best(mine, sv, si);
-    if (tid == 0) {
-      bool any = win.id != 0x7fffffff;
-      ids[(size_t)row * kp + j] = any ? win.id : -1;
-      probs[(size_t)row * kp + j] = any ? expf(win.v - gmax) / tot : 0.f;
+  const float tot = wave_sum(lsum);
+
+  LaneList L;
+  list_init(L);
+  const int ncand = nseg * kp;
+  float floor_bound = -INFINITY, bound = -INFINITY;
+  for (int c0 = 0; c0 < ncand; c0 += 64) {
+    const int i = c0 + lane;
+    float v = -INFINITY;
+    int id = 0x7fffffff;
+    if (i < ncand) {
+      const float* e = base + (size_t)(i / kp) * stride;
+      v = e[2 + i % kp];
+      id = reinterpret_cast<const int*>(e)[2 + kp + i % kp];
     }
-    for (int i = tid; i < ncand; i += 256)
-      if (ci[i] == win.id) cv[i] = -INFINITY;
-    __syncthreads();
+    if (c0 == 0) {
+      floor_bound = kth_largest_lane(v, kp, lane);
+      bound = floor_bound;
+    }
+    if (v == -INFINITY) id = 0x7fffffff;
+    // empty slots (-inf) never qualify: better() against the (-inf, INT_MAX) tail is false
+    offer(L, v, id, bound, floor_bound, kp, lane);
   }
+  if (lane < kp) {
+    const bool any = L.id != 0x7fffffff;
+    ids[(size_t)row * kp + lane] = any ? L.id : -1;
+    probs[(size_t)row * kp + lane] = any ? expf(L.v - gmax) / tot : 0.f;
+  }
+}
+
+// segments per row: enough independent waves to fill the chip (about 8 per CU), each at least one
+// block long
+int topk_segments(int rows, int vocab, int* seg_len) {
+  const int max_seg = (vocab + BLOCK - 1) / BLOCK;
+  int nseg = std::max(1, std::min(max_seg, (2048 + rows - 1) / rows));
+  int len = ((vocab + nseg - 1) / nseg + BLOCK - 1) / BLOCK * BLOCK;
+  nseg = (vocab + len - 1) / len;
+  *seg_len = len;
+  return nseg;
 }
 
 }  // namespace
 
 size_t softmax_topk_scratch_floats(int rows, int vocab, int kp) {
-  int nchunks = (vocab + CHUNK - 1) / CHUNK;
-  return (size_t)rows * nchunks * (2 + 2 * kp);
+  int max_seg = (vocab + BLOCK - 1) / BLOCK;   // upper bound of the segment count for any row count
+  return (size_t)rows * max_seg * (2 + 2 * kp);
 }
 
 hipError_t launch_softmax_topk(hipStream_t st, const float* logits, int rows, int vocab, int kp, int32_t* ids,
                                float* probs, float* scratch) {
   if (rows <= 0) return hipSuccess;
-  int nchunks = (vocab + CHUNK - 1) / CHUNK;
-  hipLaunchKernelGGL(k_topk_chunks, dim3(nchunks, rows), dim3(256), 0, st, logits, vocab, kp, nchunks, scratch);
+  int seg_len = 0;
+  const int nseg = topk_segments(rows, vocab, &seg_len);
+  const int items = rows * nseg;
+  hipLaunchKernelGGL(k_topk_stream, dim3((items + 3) / 4), dim3(256), 0, st, logits, rows, vocab, kp, nseg, seg_len,
+                     scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  size_t lds = (size_t)nchunks * kp * 8;
-  hipLaunchKernelGGL(k_topk_merge, dim3(rows), dim3(256), lds, st, scratch, kp, nchunks, ids, probs);
+  hipLaunchKernelGGL(k_topk_merge, dim3((rows + 3) / 4), dim3(256), 0, st, scratch, rows, kp, nseg, ids, probs);
   return hipGetLastError();
 }
