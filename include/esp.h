@@ -92,7 +92,10 @@ typedef struct {
   const void *final_norm;        /* [d_model]                                          */
   const void *const *wqkv;       /* [(n_q + 2 n_kv) * head_dim, d_model]: q, k, v rows */
   const void *const *wo;         /* [d_model, n_q * head_dim]                          */
-  const void *const *w_gate_up;  /* [2 d_ff, d_model]: gate rows then up rows          */
+  const void *const *w_gate_up;  /* [2 d_ff, d_model].  ESP_F32: all gate rows, then all up rows.
+                                  * ESP_BF16: blocks of 32 rows alternate (gate rows 0..31, up rows
+                                  * 0..31, gate rows 32..63, ...) before esp_pack_weight, so that the
+                                  * projection can apply the SwiGLU in its epilogue */
   const void *const *w_down;     /* [d_model, d_ff]                                    */
   const void *const *norm_attn;  /* [d_model]                                          */
   const void *const *norm_mlp;   /* [d_model]                                          */

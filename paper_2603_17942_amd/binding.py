@@ -244,7 +244,7 @@ class Engine:
             w = lw[l]
             arrs["wqkv"][l] = mat(torch.cat([w["wq"], w["wk"], w["wv"]], 0)).data_ptr()
             arrs["wo"][l] = mat(w["wo"]).data_ptr()
-            arrs["w_gate_up"][l] = mat(torch.cat([w["w_gate"], w["w_up"]], 0)).data_ptr()
+            arrs["w_gate_up"][l] = mat(self._fuse_gate_up(w["w_gate"], w["w_up"])).data_ptr()
             arrs["w_down"][l] = mat(w["w_down"]).data_ptr()
             arrs["norm_attn"][l] = dev(w["norm_attn"]).data_ptr()
             arrs["norm_mlp"][l] = dev(w["norm_mlp"]).data_ptr()
@@ -268,6 +268,16 @@ class Engine:
                                    ws_ptr, nbytes, _stream_ptr(), C.byref(ctx)), "esp_create")
         self.ctx = ctx
         self.max_batch, self.max_rows = max_batch, max_rows_per_seq
+
+    def _fuse_gate_up(self, gate: torch.Tensor, up: torch.Tensor) -> torch.Tensor:
+        """The fused gate/up matrix of esp_weights: fp32 models stack all gate rows on all up rows;
+        bf16 models alternate blocks of 32 rows (gate block j, up block j, ...), the order in which
+        the projection kernel pairs them for its SwiGLU epilogue."""
+        if self.dt != torch.bfloat16:
+            return torch.cat([gate, up], 0)
+        ff, d = gate.shape
+        assert ff % 32 == 0
+        return torch.stack([gate.reshape(ff // 32, 32, d), up.reshape(ff // 32, 32, d)], 1).reshape(2 * ff, d)
 
     def close(self):
         if getattr(self, "ctx", None):

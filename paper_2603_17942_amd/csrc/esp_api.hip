@@ -336,10 +336,15 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
       ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_o.splits, M, d, c->norm_mlp[l], m.rms_eps, c->xn)); }
-    { ESP_PROF(ESP_SITE_GEMM_LAYER);
-      ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wgu[l], c->gemm_out, M, 2 * ff, d, p_gu, pk)); }
-    { ESP_PROF(ESP_SITE_GLUE);
-      ESP_HIP(launch_swiglu(s, dt, c->gemm_out, p_gu.splits, M, ff, c->act)); }
+    if (dt == ESP_BF16) {   // gate/up projection with the SwiGLU in its epilogue (interleaved weight rows)
+      ESP_PROF(ESP_SITE_GEMM_LAYER);
+      ESP_HIP(launch_gemm_swiglu(s, c->xn, c->wgu[l], c->act, M, ff, d));
+    } else {
+      { ESP_PROF(ESP_SITE_GEMM_LAYER);
+        ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wgu[l], c->gemm_out, M, 2 * ff, d, p_gu, pk)); }
+      { ESP_PROF(ESP_SITE_GLUE);
+        ESP_HIP(launch_swiglu(s, dt, c->gemm_out, p_gu.splits, M, ff, c->act)); }
+    }
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
       ESP_HIP(launch_gemm(s, dt, c->act, nullptr, c->wdown[l], c->gemm_out, M, d, ff, p_dn, pk)); }
     const bool last = l + 1 == m.n_layers;

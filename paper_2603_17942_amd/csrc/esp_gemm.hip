@@ -26,9 +26,17 @@ namespace {
 
 
 constexpr int KC = 64;            // k per chunk
+// silu(g) * u with the hardware exponential and reciprocal (about 1 ulp each; the result is
+// rounded to bf16 next)
+__device__ __forceinline__ float silu_mul(float g, float u) {
+  return g * u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
+}
+
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
-template <int MT, int NB, int D, bool TILED, int WM, bool AMAX>   // D even; WM wave groups along M
+// EPI: epilogue -- 0 fp32 tile out, 1 per-row arg-max over the workgroup's columns, 2 SwiGLU of
+// interleaved gate/up column blocks to bf16
+template <int MT, int NB, int D, bool TILED, int WM, int EPI>   // D even; WM wave groups along M
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
@@ -169,7 +177,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   }
 
   // epilogue: lane holds column n, rows 8*(v/4) + 4*lg + v%4 of each 32x32 tile
-  if (!AMAX) {
+  if (EPI == 0) {
     float* o = out + (size_t)z * M * N;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -185,7 +193,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         }
       }
     }
-  } else {
+  } else if (EPI == 1) {
     // arg-max epilogue (LM head at the tree rows; needs splits == 1): per row the maximum over
     // this workgroup's columns, lowest column on ties.  `out` receives [n_tiles][M] pairs
     // (value, column as int bits); the logits themselves are never written.
@@ -231,6 +239,45 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         out[((size_t)ni * M + m) * 2 + 1] = __int_as_float(bi);
       }
     }
+  } else {
+    // SwiGLU epilogue (fused gate/up projection; needs splits == 1): the weight rows alternate
+    // in blocks of 32 between gate and up, so output column block 2j is gate block j and 2j+1 is
+    // up block j.  `out` is the bf16 activation matrix [M][N/2]: act = silu(gate) * up.
+    bf16_t* act = reinterpret_cast<bf16_t*>(out);
+    const int ff = N >> 1;
+    if (NB == 2) {   // both blocks in this lane's registers
+      if (n0 < N) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int m = m0 + i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+            const float g = acc[i][0][v], u = acc[i][NB - 1][v];
+            if (m < M) act[(size_t)m * ff + (n0 >> 1) + lr] = (bf16_t)silu_mul(g, u);
+          }
+      }
+    } else {         // the odd wave of a pair holds the up block: hand it over through LDS
+      float* ex = reinterpret_cast<float*>(lds);              // [2 pairs][MT*32 rows][32]
+      if (wn & 1) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            ex[((wn >> 1) * MT * 32 + i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3)) * 32 + lr] = acc[i][0][v];
+      }
+      __syncthreads();
+      if (!(wn & 1) && n0 < N) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int rl = i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+            const int m = m0 + rl;
+            const float g = acc[i][0][v], u = ex[((wn >> 1) * MT * 32 + rl) * 32 + lr];
+            if (m < M) act[(size_t)m * ff + (n0 >> 1) + lr] = (bf16_t)silu_mul(g, u);
+          }
+      }
+    }
   }
 }
 
@@ -238,20 +285,20 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
 // wave) leaves occupancy to the compiler.  The large-tile one tells it that one wave per SIMD is
 // all it will ever get, so registers go to prefetching.  (A 512-thread variant with two row groups
 // per workgroup and two waves per SIMD was measured and was not faster.)
-template <int MT, int NB, int D, bool TILED, bool AMAX>
+template <int MT, int NB, int D, bool TILED, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
                                                    int N, int K, int splits, int m_tiles, int n_tiles, int a_ld) {
   extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
-  gemm_bf16_body<MT, NB, D, TILED, 1, AMAX>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
+  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
 }
 
-template <int MT, int NB, int D, bool TILED>
+template <int MT, int NB, int D, bool TILED, int EPI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_big(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
     float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_bf16_body<MT, NB, D, TILED, 1, false>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
+  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -316,18 +363,18 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
   reinterpret_cast<uint4*>(dst)[piece] = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
 }
 
-template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), bool AMAX = false>
+template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), int EPI = 0>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
                        int N, int K, const GemmPlan& p, int a_ld = 0) {
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
   if constexpr (MT * NB >= 8)
-    hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED>), dim3(per_xcd * 8), dim3(256), lds, st,
+    hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st,
                        (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles,
                        a_ld);
   else
-    hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, AMAX>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
+    hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
                        a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld);
   return hipGetLastError();
 }
@@ -410,14 +457,35 @@ hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_ro
   GemmPlan p = gemm_plan(ESP_BF16, M, N, K);
   hipError_t e = hipErrorInvalidValue;
   switch (p.mt) {
-    case 1: e = launch_bf16<1, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
-    case 2: e = launch_bf16<2, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
-    case 3: e = launch_bf16<3, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
-    case 4: e = launch_bf16<4, 1, true, 4, true>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 1: e = launch_bf16<1, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 2: e = launch_bf16<2, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 3: e = launch_bf16<3, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    case 4: e = launch_bf16<4, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
   }
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_argmax_tiles, dim3(M), dim3(256), 0, st, scratch, p.n_tiles, M, out, out_index);
   return hipGetLastError();
+}
+
+// Fused gate/up projection + SwiGLU (bf16, packed weights whose rows alternate in blocks of 32
+// between gate and up): act[M][ff] = silu(A Wg^T) * (A Wu^T), one pass over K per workgroup.
+hipError_t launch_gemm_swiglu(hipStream_t st, const void* A, const void* W, void* act, int M, int ff, int K) {
+  if (M <= 0) return hipSuccess;
+  GemmPlan p = gemm_plan(ESP_BF16, M, 2 * ff, K);
+  p.splits = 1;
+  float* out = reinterpret_cast<float*>(act);
+#define ESP_GU_CASE(MT_, NB_)                                                                           \
+  if (p.mt == MT_ && p.nb == NB_)                                                                       \
+    return launch_bf16<MT_, NB_, true, (MT_ * NB_ >= 8 ? 2 : 4), 2>(st, A, nullptr, W, out, M, 2 * ff, K, p);
+  ESP_GU_CASE(1, 1)
+  ESP_GU_CASE(2, 1)
+  ESP_GU_CASE(3, 1)
+  ESP_GU_CASE(4, 1)
+  ESP_GU_CASE(3, 2)
+  ESP_GU_CASE(4, 2)
+  ESP_GU_CASE(5, 2)
+#undef ESP_GU_CASE
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K) {

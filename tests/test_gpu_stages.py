@@ -94,6 +94,37 @@ def test_softmax_topk_exact_ties_take_lowest_id(B):
     np.testing.assert_allclose(ps[0].cpu().numpy(), want[1], rtol=1e-5)
 
 
+def test_softmax_topk_adversarial_orders_and_masked_logits(B):
+    """Rows that defeat the streaming kernel's shortcuts: strictly ascending values (every block
+    raises the bound), descending values, -inf entries, fewer finite logits than Kp, Kp == vocab,
+    and many rows (one wave per row, several segments per row for few rows)."""
+    vocab, kp = 20000, 9
+    asc = torch.arange(vocab, dtype=torch.float32) * 1e-3
+    desc = asc.flip(0)
+    holes = synth.normal_like((vocab,), 1.0, 31, 0, "cpu", torch.float32).clone()
+    holes[::3] = float("-inf")
+    few = torch.full((vocab,), float("-inf"))
+    few[[5, 17000, 9999]] = torch.tensor([0.5, 2.0, -1.0])
+    logits = torch.stack([asc, desc, holes, few]).cuda()
+    ids, ps = B.softmax_topk(logits, kp)
+    ids, ps = ids.cpu().numpy(), ps.cpu().numpy()
+    for r in range(3):
+        want_ids, want_ps = O.softmax_topk(logits[r].cpu().numpy(), kp)
+        assert ids[r].tolist() == want_ids.tolist()
+        np.testing.assert_allclose(ps[r], want_ps, rtol=1e-4)
+    assert ids[3, :3].tolist() == [17000, 5, 9999] and np.all(ids[3, 3:] == -1) and np.all(ps[3, 3:] == 0)
+    np.testing.assert_allclose(ps[3, :3].sum(), 1.0, rtol=1e-5)
+    small = synth.normal_like((2, 8), 1.0, 32, 0, "cuda", torch.float32)
+    ids, ps = B.softmax_topk(small, 8)
+    for r in range(2):
+        want_ids, want_ps = O.softmax_topk(to_np(small)[r], 8)
+        assert ids[r].tolist() == want_ids.tolist()
+        np.testing.assert_allclose(ps[r].cpu().numpy(), want_ps, rtol=1e-5)
+    many = synth.normal_like((700, 4100), 2.0, 33, 0, "cuda", torch.float32)
+    ids, ps = B.softmax_topk(many, 10)
+    check_topk(ids.cpu().numpy(), ps.cpu().numpy(), to_np(many), 10, 1e-6)
+
+
 # ---------------------------------------------------------------------------------------- engine fixture
 @pytest.fixture(scope="module")
 def tiny_engine(B):
