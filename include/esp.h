@@ -103,10 +103,15 @@ typedef struct {
   const void *const *k_norm;     /* [head_dim], NULL unless qk_norm                    */
 } esp_weights;
 
-/* KV cache pool (device, model dtype), shared by the sequences of a batch.
- *   k: [n_layers][n_kv_heads][capacity][head_dim]
- *   v: [n_layers][n_kv_heads][capacity / 64][head_dim][64]   (slot-blocked, transposed inside
- *      a block of 64 slots, so that a tile of V arrives with slots contiguous per feature)
+/* KV cache pool (device, model dtype), shared by the sequences of a batch.  k and v each hold
+ * [n_layers][n_kv_heads] planes of capacity * head_dim elements.  A plane is a sequence of blocks
+ * of 32 slots; inside a block the elements sit in the order the matrix cores consume them
+ * (64 lanes x 8 elements per fragment), head_dim a multiple of 32:
+ *   k block: [head_dim/16][64][8]     element (slot, d) at ((d/16)*64 + ((d/8)%2)*32 + slot%32)*8 + d%8
+ *   v block: [head_dim/32][2][64][8]  element (slot, d), key = slot%32, at
+ *            (((d/32)*2 + key/16)*64 + ((key/4)%2)*32 + d%32)*8 + 4*((key/8)%2) + key%4
+ * Callers never index the pool themselves: esp_kv_store / esp_kv_load convert from and to plain
+ * [slots][head_dim] rows.
  * Sequence b owns slots [base[b], base[b] + seq_cap[b]); base[b] is a multiple of 64.
  * Slots [0, len[b]) of a sequence hold committed tokens; a forward writes the block's rows at
  * len[b] + row (scratch until committed). */

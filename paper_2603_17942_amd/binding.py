@@ -155,7 +155,7 @@ class KvCache:
         self.batch = len(caps)
         L, H, D = shape.n_layers, shape.n_kv_heads, shape.head_dim
         self.k = torch.zeros((L, H, self.capacity, D), dtype=dt, device=device)
-        self.v = torch.zeros((L, H, self.capacity // 64, D, 64), dtype=dt, device=device)
+        self.v = torch.zeros((L, H, self.capacity, D), dtype=dt, device=device)   # same plane size; block order
         self.len = torch.zeros(self.batch, dtype=torch.int32, device=device)
         self.base = torch.tensor(bases, dtype=torch.int32, device=device)
         self.seq_cap = torch.tensor(caps, dtype=torch.int32, device=device)
