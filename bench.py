@@ -258,6 +258,7 @@ def main():
     ap.add_argument("--kv-len", type=int, default=2048)
     ap.add_argument("--no-stages", action="store_true", help="skip the stage-level roofline figures")
     ap.add_argument("--no-sweep", action="store_true", help="skip the block-complexity sweep")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--fast-weights", action="store_true",
                     help="draw the weights with torch.Tensor.normal_ (one kernel per tensor) instead of the "
                          "counter-based generator; for counter-collection runs, where tens of thousands of "
@@ -274,6 +275,10 @@ def main():
 
     B.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback of the hot path)"
+    # everything runs on one non-default stream (the engine binds to the stream it is created on),
+    # so that a step can also be captured into a HIP graph
+    side = torch.cuda.Stream()
+    torch.cuda.set_stream(side)
     shape = synth.SHAPES["llama3_8b"]
     n_nodes, k, K, kp, L = 64, 4, 8, 10, args.kv_len
     t_setup = time.perf_counter()
@@ -363,6 +368,18 @@ def main():
                              "roofline": sa["roofline"],
                              "roofline_attn": sa["roofline_attn"],
                              "breakdown_ms_per_step": sa["breakdown_ms_per_step"]}
+    def graph_replay(r, eager_ms):
+        """Two consecutive steps captured into a HIP graph, replayed; same work as the eager step."""
+        n = max(args.steps // 2, 5)
+        g = r["dec"].capture_step_pair(n + 3, side)
+        ms = time_gpu(torch, g.replay, n, warm=2) / 2
+        assert r["dec"].eng.device_status() == 0
+        return {"ms_per_step": ms, "vs_eager": eager_ms / ms}
+
+    if not args.no_graph:
+        out["hip_graph_replay"] = graph_replay(main_r, sm["ms_per_step"])
+        if alt_r is not None:
+            out["alt_layout"]["hip_graph_replay"] = graph_replay(alt_r, out["alt_layout"]["ms_per_step"])
     # ordinary decode step with the same kernels, and what the paper's acceptance lengths would make of
     # the measured step-cost ratio (random weights accept nothing, so tau_measured is 1)
     ar_ms = ar_baseline(B, torch, main_r["dec"], 20)

@@ -105,6 +105,23 @@ class EspDecoder:
         self.cur, self.nxt = self.nxt, self.cur
         self.kv.len_bound += self.k + 1      # a step commits at most k+1 tokens
 
+    # ---- HIP-graph replay of the step ------------------------------------------------------------------
+    def capture_step_pair(self, n_replays: int, stream: "torch.cuda.Stream") -> "torch.cuda.CUDAGraph":
+        """Captures two consecutive steps (the block buffers swap every step, so a pair returns to
+        the same buffers) into a HIP graph on `stream`, the stream the engine was created on (not
+        the default stream).  Everything a step needs lives on the device; the one host value,
+        the cache-length bound that sizes the attention launch, is fixed here for n_replays
+        replays.  Every launch site must have run once before (kernel attributes are set on first
+        use), i.e. call step() at least twice before capturing."""
+        self.kv.len_bound += (2 * n_replays + 2) * (self.k + 1)
+        bound0 = self.kv.len_bound
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            self.step()
+            self.step()
+        self.kv.len_bound = bound0 + 2 * (self.k + 1)
+        return g
+
     def emitted(self) -> List[List[int]]:
         """Tokens emitted by the last step, per sequence (synchronises)."""
         ne = self.n_emit.cpu().tolist()

@@ -288,3 +288,48 @@ def test_bf16_loop_is_lossless_up_to_near_ties(B):
             dec.set_tree([tok], [parent])
     assert dec.eng.device_status() == 0
     assert len(out) >= 8 and accepted >= 2
+
+
+def test_hip_graph_replay_matches_eager_steps(B):
+    """A pair of steps captured into a HIP graph and replayed several times (with the program's
+    own eager work and synchronisations in between) emits exactly the tokens of the same number
+    of eager steps, and leaves the cache in the same state."""
+    from paper_2603_17942_amd import decode
+    shape = small_shape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=512, vocab=2048, n_layers=2,
+                        dtype="bf16", rope_theta=5.0e5)
+    w = synth.make_weights(shape, seed=41)
+    prompt = synth.make_prompt(90, shape.vocab, seed=42).tolist()
+    params = B.tree_params(10, 2, 3, 0, True, False, B.LAYOUT_PER_NODE)
+    n_pairs = 4
+
+    def run(use_graph):
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            dec = decode.EspDecoder(shape, w, params, 5, [1024], prefill_chunk=64)
+            dec.prefill([prompt])
+            toks = []
+            for _ in range(2):                      # every launch site runs once before the capture
+                dec.step()
+                toks.append(dec.emitted()[0])
+            g = dec.capture_step_pair(n_pairs, side) if use_graph else None
+            # the captured pair has not advanced the cache: capture records, it does not run
+            for _ in range(n_pairs):
+                if use_graph:
+                    g.replay()
+                    toks.append(("pair", dec.emitted()[0]))          # eager work + sync between replays
+                else:
+                    dec.step()
+                    dec.step()
+                    toks.append(("pair", dec.emitted()[0]))
+                _ = (dec.hidden.float().sum() + dec.kv.len.sum()).item()
+            side.synchronize()
+            state = (int(dec.kv.len[0]), dec.cur.tok[:dec.rows_per_seq].tolist(), dec.cur.parent[:dec.rows_per_seq].tolist())
+            assert dec.eng.device_status() == 0
+            k0, v0 = dec.eng.kv_load(dec.kv, 1, 0, 0, state[0])
+            dec.eng.close()
+        return toks, state, k0.float().cpu().numpy(), v0.float().cpu().numpy()
+
+    eager, graph = run(False), run(True)
+    assert graph[0] == eager[0]
+    assert graph[1] == eager[1]
+    assert np.array_equal(graph[2], eager[2]) and np.array_equal(graph[3], eager[3])
