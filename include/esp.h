@@ -210,7 +210,11 @@ esp_status esp_verify_accept(esp_ctx *ctx, const esp_block *blk, const int32_t *
  * softmax over the full vocabulary in fp32, the Kp most probable tokens per row ordered by
  * (probability descending, id ascending).  PER_NODE: rows mask(n*, i), i = 1..k.  ROOT_CHAIN:
  * rows mask(root, a+i), i = 1..k-a, with a = n_emit-1 accepted tokens.
- *   hidden   device: hidden_out of esp_tree_forward
+ *   hidden   device: hidden_out of esp_tree_forward, unchanged since that call.  For blocks of at
+ *            most 128 rows (bf16) the forward has already taken all rows through the LM head and
+ *            left the logits in the workspace; this call then reads its rows there instead of
+ *            streaming the LM-head matrix a second time (recognised by the same `hidden` pointer
+ *            and row count; any other esp_tree_forward in between invalidates it)
  *   topk_id  device [batch][k_masks][Kp] int32;  topk_p same shape fp32
  *   n_lists  device [batch] int32: number of valid lists (depths the next tree may have)
  *   logits_out NULL or device [batch][k_masks][vocab] fp32 (parity tests)

@@ -298,6 +298,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
   st = check_kv(c, kv, blk);
   if (st != ESP_OK) return st;
   if (!hidden_out || (blk->k_masks > 0 && !mask_embed)) return ESP_EINVAL;
+  c->lm_cache_hidden = nullptr;     // whatever logits an earlier forward left behind are stale now
   const esp_model_desc& m = c->m;
   const int dt = m.dtype, d = m.d_model, hq = m.n_q_heads, hkv = m.n_kv_heads, hd = m.head_dim, ff = m.d_ff;
   const int nqkv = (hq + 2 * hkv) * hd;
@@ -373,12 +374,23 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     if (p_lm.splits != 1) return ESP_ESHAPE;
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b)); }
-    if (gemm_argmax_supported(dt, Mn, m.vocab, d) &&
+    if (blk->k_masks > 0 && gemm_argmax_supported(dt, M, m.vocab, d) && (size_t)M <= c->logits_rows &&
+        gemm_argmax_scratch_floats(M, m.vocab) <= c->gemm_out_floats) {
+      // few rows (<= 128): one pass over the LM head for all block rows.  The tree rows get their
+      // arg-max from the epilogue; the logits of every row stay in the workspace, where
+      // esp_mask_topk on these hidden states finds its mask rows without a second pass over the
+      // 2*vocab*d_model bytes of the matrix.
+      ESP_PROF(ESP_SITE_LM_HEAD);
+      ESP_HIP(launch_gemm_argmax(s, hidden_out, nullptr, c->lm_head, M, m.vocab, d, c->gemm_out, node_argmax,
+                                 c->idx_b, 0, c->logits, c->idx_a, Mn));
+      c->lm_cache_hidden = hidden_out;
+      c->lm_cache_rows = M;
+    } else if (gemm_argmax_supported(dt, Mn, m.vocab, d) &&
         gemm_argmax_scratch_floats(Mn, m.vocab) <= c->logits_rows * (size_t)m.vocab) {
       // arg-max in the GEMM epilogue: the [rows, vocab] logits are never written
       ESP_PROF(ESP_SITE_LM_HEAD);
       ESP_HIP(launch_gemm_argmax(s, hidden_out, c->idx_a, c->lm_head, Mn, m.vocab, d, c->logits, node_argmax,
-                                 c->idx_b));
+                                 c->idx_b, 0, nullptr, nullptr, Mn));
     } else {
       { ESP_PROF(ESP_SITE_LM_HEAD);
         ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm, pk)); }
@@ -418,6 +430,13 @@ esp_status esp_mask_topk(esp_ctx* c, const esp_block* blk, const int32_t* star_r
   BlockDev bd = to_dev(blk);
   { ESP_PROF(ESP_SITE_TREE);
     ESP_HIP(launch_mask_rows(s, bd, star_row, n_emit, c->idx_a, n_lists)); }
+  if (!logits_out && c->lm_cache_hidden == hidden && c->lm_cache_rows == blk->batch * blk->rows_per_seq) {
+    // the forward that produced `hidden` left the logits of all its rows in the workspace
+    ESP_PROF(ESP_SITE_TOPK);
+    ESP_HIP(launch_softmax_topk(s, c->logits, rows, m.vocab, Kp, topk_id, topk_p, c->topk_scratch, c->idx_a));
+    return ESP_OK;
+  }
+  c->lm_cache_hidden = nullptr;          // c->logits is about to be overwritten
   const GemmPlan p_lm = gemm_plan(m.dtype, rows, m.vocab, m.d_model);
   if (p_lm.splits != 1) return ESP_ESHAPE;
   float* lg = logits_out ? logits_out : c->logits;

@@ -34,13 +34,13 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
-// EPI: epilogue -- 0 fp32 tile out, 1 per-row arg-max over the workgroup's columns, 2 SwiGLU of
-// interleaved gate/up column blocks to bf16
+// EPI: epilogue -- 0 fp32 tile out, 1 per-row arg-max over the workgroup's columns (pairs to out),
+// 2 SwiGLU of interleaved gate/up column blocks to bf16, 3 fp32 tile to out and arg-max pairs to out2
 template <int MT, int NB, int D, bool TILED, int WM, int EPI>   // D even; WM wave groups along M
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
-                                               int m_tiles, int n_tiles, int a_ld) {
+                                               int m_tiles, int n_tiles, int a_ld, float* __restrict__ out2) {
   // XCD-aware logical id: consecutive hardware ids go to different XCDs, so give each XCD a
   // contiguous range of tiles (tiles sharing weight rows then share an L2).
   const int total = m_tiles * n_tiles * splits;
@@ -177,7 +177,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   }
 
   // epilogue: lane holds column n, rows 8*(v/4) + 4*lg + v%4 of each 32x32 tile
-  if (EPI == 0) {
+  if (EPI == 0 || EPI == 3) {
     float* o = out + (size_t)z * M * N;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -193,7 +193,8 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         }
       }
     }
-  } else if (EPI == 1) {
+  }
+  if (EPI == 1 || EPI == 3) {
     // arg-max epilogue (LM head at the tree rows; needs splits == 1): per row the maximum over
     // this workgroup's columns, lowest column on ties.  `out` receives [n_tiles][M] pairs
     // (value, column as int bits); the logits themselves are never written.
@@ -234,12 +235,14 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
       }
       const int m = mt0 + rl;
+      float* pairs = EPI == 3 ? out2 : out;
       if (m < M) {
-        out[((size_t)ni * M + m) * 2 + 0] = best;
-        out[((size_t)ni * M + m) * 2 + 1] = __int_as_float(bi);
+        pairs[((size_t)ni * M + m) * 2 + 0] = best;
+        pairs[((size_t)ni * M + m) * 2 + 1] = __int_as_float(bi);
       }
     }
-  } else {
+  }
+  if (EPI == 2) {
     // SwiGLU epilogue (fused gate/up projection; needs splits == 1): the weight rows alternate
     // in blocks of 32 between gate and up, so output column block 2j is gate block j and 2j+1 is
     // up block j.  `out` is the bf16 activation matrix [M][N/2]: act = silu(gate) * up.
@@ -288,17 +291,19 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
 template <int MT, int NB, int D, bool TILED, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
-                                                   int N, int K, int splits, int m_tiles, int n_tiles, int a_ld) {
+                                                   int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
+                                                   float* __restrict__ out2) {
   extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
-  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
+  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld, out2);
 }
 
 template <int MT, int NB, int D, bool TILED, int EPI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_big(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
-    float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld) {
+    float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
+    float* __restrict__ out2) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld);
+  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld, out2);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -365,17 +370,17 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
 
 template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), int EPI = 0>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
-                       int N, int K, const GemmPlan& p, int a_ld = 0) {
+                       int N, int K, const GemmPlan& p, int a_ld = 0, float* out2 = nullptr) {
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
   if constexpr (MT * NB >= 8)
     hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st,
                        (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles,
-                       a_ld);
+                       a_ld, out2);
   else
     hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
-                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld);
+                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2);
   return hipGetLastError();
 }
 
@@ -413,12 +418,13 @@ namespace {
 
 // arg-max over the per-tile partials written by the AMAX epilogue: one workgroup per row
 __global__ __launch_bounds__(256) void k_argmax_tiles(const float* __restrict__ part, int n_tiles, int M,
-                                                      int32_t* __restrict__ out, const int32_t* __restrict__ out_index) {
+                                                      const int32_t* __restrict__ row_map, int32_t* __restrict__ out,
+                                                      const int32_t* __restrict__ out_index) {
   __shared__ float sv[4];
   __shared__ int si[4];
-  const int m = blockIdx.x;
-  const int dst = out_index ? out_index[m] : m;
+  const int dst = out_index ? out_index[blockIdx.x] : (int)blockIdx.x;
   if (dst < 0) return;
+  const int m = row_map ? max(row_map[blockIdx.x], 0) : (int)blockIdx.x;   // row of the pair table
   float best = -INFINITY;
   int bi = 0x7fffffff;
   for (int t = threadIdx.x; t < n_tiles; t += 256) {
@@ -453,17 +459,27 @@ bool gemm_argmax_supported(int dtype, int M, int N, int K) {
 size_t gemm_argmax_scratch_floats(int M, int N) { return (size_t)((N + 127) / 128) * M * 2; }
 
 hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
-                              int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld) {
+                              int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld,
+                              float* logits_out, const int32_t* arg_rows, int n_arg) {
   GemmPlan p = gemm_plan(ESP_BF16, M, N, K);
   hipError_t e = hipErrorInvalidValue;
+  // without logits_out: pairs only (the logits are never written); with it: the fp32 logits of all M
+  // rows as well
+#define ESP_AMAX_CASE(MT_)                                                                                     \
+  case MT_:                                                                                                    \
+    e = logits_out ? launch_bf16<MT_, 1, true, 4, 3>(st, A, a_rows, W, logits_out, M, N, K, p, a_ld, scratch)  \
+                   : launch_bf16<MT_, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld);             \
+    break;
   switch (p.mt) {
-    case 1: e = launch_bf16<1, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
-    case 2: e = launch_bf16<2, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
-    case 3: e = launch_bf16<3, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
-    case 4: e = launch_bf16<4, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld); break;
+    ESP_AMAX_CASE(1)
+    ESP_AMAX_CASE(2)
+    ESP_AMAX_CASE(3)
+    ESP_AMAX_CASE(4)
   }
+#undef ESP_AMAX_CASE
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_argmax_tiles, dim3(M), dim3(256), 0, st, scratch, p.n_tiles, M, out, out_index);
+  // out[out_index[i]] = arg-max of row arg_rows[i] (or of row i), i < n_arg
+  hipLaunchKernelGGL(k_argmax_tiles, dim3(n_arg), dim3(256), 0, st, scratch, p.n_tiles, M, arg_rows, out, out_index);
   return hipGetLastError();
 }
 

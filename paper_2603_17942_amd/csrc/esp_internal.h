@@ -75,8 +75,11 @@ hipError_t launch_gemm_swiglu(hipStream_t st, const void* A, const void* W, void
 // LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows, one split)
 bool gemm_argmax_supported(int dtype, int M, int N, int K);
 size_t gemm_argmax_scratch_floats(int M, int N);
+// logits_out == NULL: arg-max of each of the M rows (out[out_index[m]]), logits never written.
+// logits_out != NULL: also writes the fp32 logits [M][N]; arg-max only for the n_arg rows arg_rows[i].
 hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
-                              int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld = 0);
+                              int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld,
+                              float* logits_out, const int32_t* arg_rows, int n_arg);
 
 // ---- elementwise / glue (esp_elementwise.hip) ----------------------------------------------
 struct BlockDev {   // device-side view of esp_block + esp_kv scalars, passed by value
@@ -122,8 +125,9 @@ hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const
 
 // ---- softmax + top-k (esp_topk.hip) -----------------------------------------------------------
 size_t softmax_topk_scratch_floats(int rows, int vocab, int kp);
+// row_map (nullable): logits row of output row r is row_map[r] (negative: 0)
 hipError_t launch_softmax_topk(hipStream_t st, const float* logits, int rows, int vocab, int kp, int32_t* ids,
-                               float* probs, float* scratch);
+                               float* probs, float* scratch, const int32_t* row_map = nullptr);
 
 // ---- tree logic (esp_tree.hip) -------------------------------------------------------------------
 hipError_t launch_block_from_tree(hipStream_t st, int batch, int rows_per_seq, int k, int layout, int anc_words,
@@ -159,6 +163,10 @@ struct esp_ctx {
   void* act;         // T [Mmax][d_ff]
   float* gemm_out;   // fp32 split-K partials of the largest layer GEMM
   float* attn_part;  // attention split partials
+  // logits of all block rows left in `logits` by the last esp_tree_forward (bf16, <= 128 rows), for
+  // esp_mask_topk on the same hidden states: the hidden buffer they came from and the row count
+  const void* lm_cache_hidden = nullptr;
+  int lm_cache_rows = 0;
   float* rope_tab;   // [Mmax][hd/2][2] cos, sin
   float* logits;     // fp32 [logits_rows][vocab]
   float* topk_scratch;

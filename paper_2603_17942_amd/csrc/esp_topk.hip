@@ -90,13 +90,14 @@ __device__ __forceinline__ void offer(LaneList& L, float v, int my_id, float& bo
 
 // scratch per (row, segment): [max, sum, v_0..v_{kp-1}, id_0..id_{kp-1}] as 2 + 2*kp words
 __global__ __launch_bounds__(256) void k_topk_stream(const float* __restrict__ logits, int rows, int vocab, int kp,
-                                                     int nseg, int seg_len, float* __restrict__ scratch) {
+                                                     int nseg, int seg_len, float* __restrict__ scratch,
+                                                     const int32_t* __restrict__ row_map) {
   const int lane = threadIdx.x & 63;
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (item >= rows * nseg) return;
   const int row = item / nseg, seg = item % nseg;
   const int start = seg * seg_len, end = min(vocab, start + seg_len);
-  const float* p = logits + (size_t)row * vocab;
+  const float* p = logits + (size_t)(row_map ? max(row_map[row], 0) : row) * vocab;
   const bool vec4 = (vocab & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
   const int nblocks = (max(end - start, 0) + BLOCK - 1) / BLOCK;
 
@@ -227,13 +228,13 @@ size_t softmax_topk_scratch_floats(int rows, int vocab, int kp) {
 }
 
 hipError_t launch_softmax_topk(hipStream_t st, const float* logits, int rows, int vocab, int kp, int32_t* ids,
-                               float* probs, float* scratch) {
+                               float* probs, float* scratch, const int32_t* row_map) {
   if (rows <= 0) return hipSuccess;
   int seg_len = 0;
   const int nseg = topk_segments(rows, vocab, &seg_len);
   const int items = rows * nseg;
   hipLaunchKernelGGL(k_topk_stream, dim3((items + 3) / 4), dim3(256), 0, st, logits, rows, vocab, kp, nseg, seg_len,
-                     scratch);
+                     scratch, row_map);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_topk_merge, dim3((rows + 3) / 4), dim3(256), 0, st, scratch, rows, kp, nseg, ids, probs);
