@@ -340,6 +340,33 @@ def calls_reduction_percent(tau: float) -> float:
 
 
 # --------------------------------------------------------------------------------------
+# sample matching at temperature 1 (Sec. 4 "Experiments", App. "Impact of Sampling")
+# --------------------------------------------------------------------------------------
+def counter_uniform(seed: int, position: int, ids: np.ndarray) -> np.ndarray:
+    """Counter-based uniform numbers in (0, 1), one per (seed, position, token id): a 32-bit
+    integer mix (multiply-xorshift finaliser of the MurmurHash3 family) of the three
+    counters, of which the top 24 bits are used, centred in their cell.  The GPU path
+    implements the same generator; random numbers are inputs of the method, not part of it."""
+    x = (np.asarray(ids, dtype=np.uint64) * 0x9E3779B1 + np.uint64(position & 0xFFFFFFFF) * 0x85EBCA77
+         + np.uint64(seed & 0xFFFFFFFF) * 0xC2B2AE3D) & 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x85EBCA6B) & 0xFFFFFFFF
+    x ^= x >> 13
+    x = (x * 0xC2B2AE35) & 0xFFFFFFFF
+    x ^= x >> 16
+    return ((x >> 8).astype(np.float64) + 0.5) / float(1 << 24)
+
+
+def sample_token(logits_row: np.ndarray, seed: int, position: int) -> int:
+    """One draw from softmax(logits) at temperature 1 by the Gumbel-max rule: the arg-max of
+    logit + g with g = -ln(-ln u) i.i.d. standard Gumbel is distributed as the softmax.
+    `position` is the absolute position of the token being drawn, so the draw at a position
+    is the same whether the position is reached by plain decoding or inside a tree."""
+    u = counter_uniform(seed, position, np.arange(len(logits_row)))
+    return argmax_lowest(as_f64(logits_row) - np.log(-np.log(u)))
+
+
+# --------------------------------------------------------------------------------------
 # proposal: softmax + Top-K' (Sec. 2 Eq. 2, Sec. 3.3)
 # --------------------------------------------------------------------------------------
 def softmax_topk(logits_row: np.ndarray, kp: int):
@@ -495,15 +522,22 @@ def round_like(x: np.ndarray, store_dtype: str) -> np.ndarray:
 
 
 def esp_step(model: Model, st: DecodeState, params: TreeParams, layout: int, kp: int,
-             store_dtype: str = "f64", ema_lambda: float = 0.0) -> StepResult:
+             store_dtype: str = "f64", ema_lambda: float = 0.0,
+             sample_seed: Optional[int] = None) -> StepResult:
     """One speculate-and-verify step: forward tree + masks, verify, commit the accepted
     rows' K/V, take Top-K' at the mask rows that follow the accepted node, build the next
-    tree.  Mutates `st` to the state before the next step."""
+    tree.  Mutates `st` to the state before the next step.  With sample_seed the base
+    model's token after node r is a temperature-1 sample (sample matching) instead of the
+    arg-max; the token drawn for a position does not depend on how it is reached."""
     blk = make_block(st.tok, st.parent, params.k, layout)
     logits, _, k_new, v_new = tree_forward(model, blk, st.mask_embed, st.k_cache, st.v_cache,
                                            st.cache_len)
     n = blk.n_nodes
-    g = np.asarray([argmax_lowest(logits[r]) for r in range(n)], dtype=np.int64)
+    if sample_seed is None:
+        g = np.asarray([argmax_lowest(logits[r]) for r in range(n)], dtype=np.int64)
+    else:   # node r sits at position cache_len + depth(r); its successor one further
+        g = np.asarray([sample_token(logits[r], sample_seed, st.cache_len + int(blk.depth[r]) + 1)
+                        for r in range(n)], dtype=np.int64)
     n_star, accepted, emitted = verify_accept(blk.tok, blk.parent, g)
     # commit: root then the accepted rows, in path order, become cache slots L, L+1, ...
     for l in range(model.n_layers):
@@ -551,7 +585,8 @@ def prefill(model: Model, prompt: Sequence[int], store_dtype: str = "f64"):
 
 
 def esp_generate(model: Model, prompt: Sequence[int], n_new: int, params: TreeParams,
-                 layout: int, kp: int, store_dtype: str = "f64", ema_lambda: float = 0.0):
+                 layout: int, kp: int, store_dtype: str = "f64", ema_lambda: float = 0.0,
+                 sample_seed: Optional[int] = None):
     """Prompt -> at least n_new tokens by repeated esp_step.  The first step has the root
     alone (plus its masks), so it emits one token and seeds the first tree.
     Returns (tokens[:n_new], per-step results)."""
@@ -561,15 +596,16 @@ def esp_generate(model: Model, prompt: Sequence[int], n_new: int, params: TreePa
     out: List[int] = []
     steps = []
     while len(out) < n_new:
-        res = esp_step(model, st, params, layout, kp, store_dtype, ema_lambda)
+        res = esp_step(model, st, params, layout, kp, store_dtype, ema_lambda, sample_seed)
         out.extend(res.emitted)
         steps.append(res)
     return out[:n_new], steps
 
 
-def greedy_generate(model: Model, prompt: Sequence[int], n_new: int, store_dtype: str = "f64"):
-    """Plain autoregressive greedy decoding (Sec. 2 Eq. 1 with argmax): one token per
-    model call, through the sequential code path."""
+def greedy_generate(model: Model, prompt: Sequence[int], n_new: int, store_dtype: str = "f64",
+                    sample_seed: Optional[int] = None):
+    """Plain autoregressive decoding (Sec. 2 Eq. 1): one token per model call, through the
+    sequential code path; arg-max, or with sample_seed a temperature-1 sample per position."""
     kc, vc, L = prefill(model, prompt, store_dtype)
     emb = model.weights["embed"]
     cur = int(prompt[-1])
@@ -580,6 +616,6 @@ def greedy_generate(model: Model, prompt: Sequence[int], n_new: int, store_dtype
             kc[l] = np.concatenate([kc[l][:L], round_like(k_rows[l], store_dtype)], axis=0)
             vc[l] = np.concatenate([vc[l][:L], round_like(v_rows[l], store_dtype)], axis=0)
         L += 1
-        cur = argmax_lowest(logits[0])
+        cur = argmax_lowest(logits[0]) if sample_seed is None else sample_token(logits[0], sample_seed, L)
         out.append(cur)
     return out

@@ -143,3 +143,65 @@ def test_generate_wrapper_equals_greedy():
                                 O.LAYOUT_PER_NODE, 6)
     assert out == O.greedy_generate(m, prompt, 8)
     assert sum(len(s.emitted) for s in steps) >= 8
+
+
+# ---------------------------------------------------------------------------------------------
+# sample matching (temperature 1)
+# ---------------------------------------------------------------------------------------------
+def test_counter_uniform_is_a_uniform_stream_in_the_open_interval():
+    u = O.counter_uniform(7, 3, np.arange(200000))
+    assert u.min() > 0.0 and u.max() < 1.0
+    assert abs(u.mean() - 0.5) < 4 * np.sqrt(1 / 12 / len(u))
+    hist = np.histogram(u, bins=16, range=(0, 1))[0] / len(u)
+    assert np.all(np.abs(hist - 1 / 16) < 5 * np.sqrt((1 / 16) * (15 / 16) / len(u)))
+    # the three counters all matter
+    assert not np.array_equal(u[:64], O.counter_uniform(8, 3, np.arange(64)))
+    assert not np.array_equal(u[:64], O.counter_uniform(7, 4, np.arange(64)))
+    # lag-1 correlation over consecutive ids is that of independent draws
+    c = np.corrcoef(u[:-1], u[1:])[0, 1]
+    assert abs(c) < 5 / np.sqrt(len(u))
+
+
+def test_sample_token_follows_the_softmax_distribution():
+    """The arg-max of logit + standard Gumbel noise is a draw from softmax(logits): frequencies
+    over many positions against the closed form (a wrong sign, a missing logarithm or a
+    temperature other than 1 all fail)."""
+    logits = np.array([1.5, -0.3, 0.0, 2.2, -4.0, 0.9])
+    p = O.softmax(logits)
+    n = 60000
+    draws = np.array([O.sample_token(logits, 11, pos) for pos in range(n)])
+    freq = np.bincount(draws, minlength=len(logits)) / n
+    assert np.all(np.abs(freq - p) < 4.5 * np.sqrt(p * (1 - p) / n))
+    # a draw is a function of (seed, position) only
+    assert O.sample_token(logits, 11, 123) == draws[123]
+
+
+@pytest.mark.parametrize("layout,width", [(O.LAYOUT_PER_NODE, 1), (O.LAYOUT_ROOT_CHAIN, 0)])
+def test_sampled_esp_loop_reproduces_plain_sampled_decoding(layout, width):
+    """Losslessness under sample matching: with the draw of every position fixed by
+    (seed, position), the ESP loop emits the token sequence of one-token-at-a-time sampling,
+    including steps whose tree carries the true continuation."""
+    shape = small_shape()
+    w = synth.make_weights(shape, seed=71, unit_gains=False)
+    m = oracle_model(shape, w)
+    prompt = synth.make_prompt(8, shape.vocab, seed=72).numpy()
+    n_new, seed = 14, 5
+    ref = O.greedy_generate(m, prompt, n_new + 6, sample_seed=seed)
+    assert ref != O.greedy_generate(m, prompt, n_new + 6)            # it really samples
+    params = O.TreeParams(B=7, k=2, K=3, expand_width=width)
+    kc, vc, L = O.prefill(m, prompt)
+    st = O.DecodeState(kc, vc, L, np.asarray([prompt[-1]]), np.asarray([-1]),
+                       O.mask_mean_init(m, prompt, params.k))
+    out, accepted_total, step = [], 0, 0
+    rng = np.random.default_rng(4)
+    while len(out) < n_new:
+        res = O.esp_step(m, st, params, layout, 5, sample_seed=seed)
+        out.extend(res.emitted)
+        accepted_total += len(res.accepted)
+        step += 1
+        if step % 2 == 1:
+            tok, parent = _planted_tree(shape.vocab, ref[len(out):], 2, 1, rng)
+            tok[0] = int(st.tok[0])
+            st.tok, st.parent = np.asarray(tok), np.asarray(parent)
+    assert out[:n_new] == ref[:n_new]
+    assert accepted_total >= 4
