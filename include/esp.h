@@ -180,6 +180,16 @@ esp_status esp_last_device_status(esp_ctx *ctx, int32_t *host_out);
 
 /* ---- the four calls of a step ------------------------------------------------------------ */
 
+/* Sample matching (the paper's temperature-1 mode, Sec. 4 / appendix on sampling): when enabled,
+ * node_argmax[r] of esp_tree_forward is not the arg-max but a temperature-1 draw of the token that
+ * follows row r, taken as arg-max over the vocabulary of logit + Gumbel noise.  The noise is a
+ * counter-based function of (seed, absolute position of the drawn token, token id), so the draw at a
+ * position is the same whether that position is reached by one-token-at-a-time decoding or inside a
+ * tree, and esp_verify_accept (exact match against the draws) stays lossless with respect to
+ * sampling with the same seed.  Disabled (greedy) after esp_create.  Host state only; applies to
+ * later esp_tree_forward calls on this context. */
+esp_status esp_set_sampling(esp_ctx *ctx, int32_t enabled, uint32_t seed);
+
 /* Forward of all rows of `blk` (Sec. 3.3): h0 = embed[tok] on node rows, mask_embed[j-1] on mask
  * rows (Sec. 3.1); per layer RMSNorm, QKV, optional QK-norm, rotary at position len[b]+depth,
  * K/V of the rows written to cache slots len[b]+row, tree-masked grouped-query attention over

@@ -345,7 +345,8 @@ def calls_reduction_percent(tau: float) -> float:
 def counter_uniform(seed: int, position: int, ids: np.ndarray) -> np.ndarray:
     """Counter-based uniform numbers in (0, 1), one per (seed, position, token id): a 32-bit
     integer mix (multiply-xorshift finaliser of the MurmurHash3 family) of the three
-    counters, of which the top 24 bits are used, centred in their cell.  The GPU path
+    counters, of which the top 23 bits are used, centred in their cell (so that the value is
+    exact in float32 as well).  The GPU path
     implements the same generator; random numbers are inputs of the method, not part of it."""
     x = (np.asarray(ids, dtype=np.uint64) * 0x9E3779B1 + np.uint64(position & 0xFFFFFFFF) * 0x85EBCA77
          + np.uint64(seed & 0xFFFFFFFF) * 0xC2B2AE3D) & 0xFFFFFFFF
@@ -354,7 +355,7 @@ def counter_uniform(seed: int, position: int, ids: np.ndarray) -> np.ndarray:
     x ^= x >> 13
     x = (x * 0xC2B2AE35) & 0xFFFFFFFF
     x ^= x >> 16
-    return ((x >> 8).astype(np.float64) + 0.5) / float(1 << 24)
+    return ((x >> 9).astype(np.float64) + 0.5) / float(1 << 23)
 
 
 def sample_token(logits_row: np.ndarray, seed: int, position: int) -> int:

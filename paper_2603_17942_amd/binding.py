@@ -60,7 +60,7 @@ EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
            "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_kv_store", "esp_kv_load",
            "esp_gemm_scratch_bytes", "esp_gemm", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
-           "esp_softmax_topk", "esp_profile_enable", "esp_profile_read", "esp_pack_weight"]
+           "esp_softmax_topk", "esp_profile_enable", "esp_profile_read", "esp_pack_weight", "esp_set_sampling"]
 SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
 
 _lib = None
@@ -107,6 +107,7 @@ def load_library() -> C.CDLL:
     lib.esp_softmax_topk_scratch_bytes.argtypes = [_i32, _i32, _i32]
     lib.esp_softmax_topk.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, C.c_size_t]
     lib.esp_profile_enable.argtypes = [_vp, C.c_uint32]
+    lib.esp_set_sampling.argtypes = [_vp, C.c_int32, C.c_uint32]
     lib.esp_profile_read.argtypes = [_vp, _i32, P(_i64), P(C.c_double)]
     for name in EXPORTS:
         getattr(lib, name)          # AttributeError here = a declared entry point is not exported
@@ -349,6 +350,10 @@ class Engine:
         b, k = blk.struct(), kv.struct()
         _check(self.lib.esp_attn_tree(self.ctx, C.byref(b), C.byref(k), layer, _ptr(q), _ptr(out)),
                "esp_attn_tree")
+
+    def set_sampling(self, enabled: bool, seed: int = 0):
+        """Sample matching (temperature 1) instead of greedy verification for later forwards."""
+        _check(self.lib.esp_set_sampling(self.ctx, int(bool(enabled)), int(seed) & 0xFFFFFFFF), "esp_set_sampling")
 
     def profile_enable(self, sites: Sequence[str]):
         mask = 0

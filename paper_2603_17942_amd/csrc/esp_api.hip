@@ -10,7 +10,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t elt(int dtype) { return dtype == ESP_F32 ? 4 : 2; }
 
 struct WsLayout {
-  size_t h, xn, q, attn_out, act, gemm_out, attn_part, rope_tab, logits, topk_scratch, idx_a, idx_b, status, total;
+  size_t h, xn, q, attn_out, act, gemm_out, attn_part, rope_tab, logits, topk_scratch, idx_a, idx_b, idx_c, idx_d, status, total;
   size_t gemm_out_floats, attn_part_floats, logits_rows;
 };
 
@@ -71,6 +71,8 @@ WsLayout ws_layout(const esp_model_desc* m, int max_batch, int max_rows, int64_t
   w.topk_scratch = take(softmax_topk_scratch_floats(max_batch * ESP_MAX_MASKS, m->vocab, ESP_MAX_TOPK) * 4);
   w.idx_a = take(std::max<size_t>(M, (size_t)max_batch * ESP_MAX_MASKS) * 4);
   w.idx_b = take(std::max<size_t>(M, (size_t)max_batch * ESP_MAX_MASKS) * 4);
+  w.idx_c = take(std::max<size_t>(M, (size_t)max_batch * ESP_MAX_MASKS) * 4);
+  w.idx_d = take(std::max<size_t>(M, (size_t)max_batch * ESP_MAX_MASKS) * 4);
   w.status = take(256);
   w.total = off;
   return w;
@@ -228,6 +230,7 @@ esp_status esp_create(const esp_model_desc* m, const esp_weights* w, int32_t max
   c->rope_tab = (float*)(c->ws + L.rope_tab); c->logits = (float*)(c->ws + L.logits);
   c->topk_scratch = (float*)(c->ws + L.topk_scratch);
   c->idx_a = (int32_t*)(c->ws + L.idx_a); c->idx_b = (int32_t*)(c->ws + L.idx_b);
+  c->idx_c = (int32_t*)(c->ws + L.idx_c); c->idx_d = (int32_t*)(c->ws + L.idx_d);
   c->status = (int32_t*)(c->ws + L.status);
   c->gemm_out_floats = L.gemm_out_floats; c->attn_part_floats = L.attn_part_floats; c->logits_rows = L.logits_rows;
   if (hipMemsetAsync(c->status, 0, 256, c->stream) != hipSuccess) {
@@ -287,6 +290,13 @@ esp_status esp_last_device_status(esp_ctx* ctx, int32_t* host_out) {
     ESP_HIP(hipMemcpyAsync(ctx->status, &zero, 4, hipMemcpyHostToDevice, ctx->stream));
     ESP_HIP(hipStreamSynchronize(ctx->stream));
   }
+  return ESP_OK;
+}
+
+esp_status esp_set_sampling(esp_ctx* c, int32_t enabled, uint32_t seed) {
+  if (!c) return ESP_EINVAL;
+  c->sample_on = enabled ? 1 : 0;
+  c->sample_seed = seed;
   return ESP_OK;
 }
 
@@ -362,9 +372,9 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     if (node_argmax) {
       const int nb = nodes_bound(blk);
       ESP_PROF(ESP_SITE_GLUE);
-      ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b));
+      ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b, kd.len, c->idx_d));
       ESP_HIP(launch_argmax(s, logits_dbg, (size_t)m.vocab, c->idx_a, blk->batch * nb, m.vocab, node_argmax,
-                            c->idx_b));
+                            c->idx_b, c->sample_on ? c->idx_d : nullptr, c->sample_seed));
     }
   } else if (node_argmax) {
     const int nb = nodes_bound(blk);
@@ -372,8 +382,10 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     if ((size_t)Mn > c->logits_rows) return ESP_ECAPACITY;
     const GemmPlan p_lm = gemm_plan(dt, Mn, m.vocab, d);
     if (p_lm.splits != 1) return ESP_ESHAPE;
+    const int32_t* draw_list = c->sample_on ? c->idx_d : nullptr;   // draw positions per node-list entry
     { ESP_PROF(ESP_SITE_GLUE);
-      ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b)); }
+      ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b, kd.len, c->idx_d));
+      if (c->sample_on) ESP_HIP(launch_row_positions(s, bd, kd.len, c->idx_c)); }
     if (blk->k_masks > 0 && gemm_argmax_supported(dt, M, m.vocab, d) && (size_t)M <= c->logits_rows &&
         gemm_argmax_scratch_floats(M, m.vocab) <= c->gemm_out_floats) {
       // few rows (<= 128): one pass over the LM head for all block rows.  The tree rows get their
@@ -382,7 +394,8 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
       // 2*vocab*d_model bytes of the matrix.
       ESP_PROF(ESP_SITE_LM_HEAD);
       ESP_HIP(launch_gemm_argmax(s, hidden_out, nullptr, c->lm_head, M, m.vocab, d, c->gemm_out, node_argmax,
-                                 c->idx_b, 0, c->logits, c->idx_a, Mn));
+                                 c->idx_b, 0, c->logits, c->idx_a, Mn, c->sample_on ? c->idx_c : nullptr,
+                                 c->sample_seed));
       c->lm_cache_hidden = hidden_out;
       c->lm_cache_rows = M;
     } else if (gemm_argmax_supported(dt, Mn, m.vocab, d) &&
@@ -390,12 +403,13 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
       // arg-max in the GEMM epilogue: the [rows, vocab] logits are never written
       ESP_PROF(ESP_SITE_LM_HEAD);
       ESP_HIP(launch_gemm_argmax(s, hidden_out, c->idx_a, c->lm_head, Mn, m.vocab, d, c->logits, node_argmax,
-                                 c->idx_b, 0, nullptr, nullptr, Mn));
+                                 c->idx_b, 0, nullptr, nullptr, Mn, draw_list, c->sample_seed));
     } else {
       { ESP_PROF(ESP_SITE_LM_HEAD);
         ESP_HIP(launch_gemm(s, dt, hidden_out, c->idx_a, c->lm_head, c->logits, Mn, m.vocab, d, p_lm, pk)); }
       { ESP_PROF(ESP_SITE_GLUE);
-        ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b)); }
+        ESP_HIP(launch_argmax(s, c->logits, (size_t)m.vocab, nullptr, Mn, m.vocab, node_argmax, c->idx_b, draw_list,
+                              c->sample_seed)); }
     }
   }
   return ESP_OK;

@@ -242,7 +242,8 @@ hipError_t launch_swiglu(hipStream_t st, int dtype, const float* part, int split
 // ---- argmax over the vocabulary, lowest id on ties ------------------------------------------------
 __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, size_t row_stride,
                                                 const int32_t* __restrict__ row_map, int vocab,
-                                                int32_t* __restrict__ out, const int32_t* __restrict__ out_index) {
+                                                int32_t* __restrict__ out, const int32_t* __restrict__ out_index,
+                                                const int32_t* __restrict__ draw_pos, uint32_t seed) {
   __shared__ float sv[4];
   __shared__ int si[4];
   const int m = blockIdx.x;
@@ -250,10 +251,13 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
   if (dst < 0) return;
   const size_t src = row_map ? (size_t)row_map[m] : (size_t)m;
   const float* p = logits + src * row_stride;
+  const bool draw = draw_pos != nullptr;
+  const uint32_t pos = draw ? (uint32_t)draw_pos[m] : 0u;
   float best = -INFINITY;
   int bi = 0x7fffffff;
   for (int i = threadIdx.x; i < vocab; i += 256) {
     float v = p[i];
+    if (draw) v += gumbel_noise(seed, pos, (uint32_t)i);
     if (v > best) { best = v; bi = i; }   // ascending i per thread: first maximum is kept
   }
 #pragma unroll
@@ -272,28 +276,45 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 }
 
 hipError_t launch_argmax(hipStream_t st, const float* logits, size_t row_stride, const int32_t* row_map,
-                         int n_rows_out, int vocab, int32_t* out, const int32_t* out_index) {
+                         int n_rows_out, int vocab, int32_t* out, const int32_t* out_index,
+                         const int32_t* draw_pos, uint32_t seed) {
   if (n_rows_out <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_argmax, dim3(n_rows_out), dim3(256), 0, st, logits, row_stride, row_map, vocab, out,
-                     out_index);
+                     out_index, draw_pos, seed);
   return hipGetLastError();
 }
 
 // gather lists for the LM head over node rows: logical row m = seq*max_nodes + i
-__global__ void k_node_rows(BlockDev b, int max_nodes, int32_t* a_rows, int32_t* out_rows) {
+__global__ void k_node_rows(BlockDev b, int max_nodes, int32_t* a_rows, int32_t* out_rows,
+                            const int32_t* __restrict__ kv_len, int32_t* pos_list) {
   int m = blockIdx.x * blockDim.x + threadIdx.x;
   if (m >= b.batch * max_nodes) return;
   int seq = m / max_nodes, i = m % max_nodes;
   int nn = b.n_nodes[seq];
   bool live = i < nn && nn <= b.n_rows[seq] && b.n_rows[seq] <= b.rows_per_seq;
-  a_rows[m] = seq * b.rows_per_seq + (live ? i : 0);
+  const int row = seq * b.rows_per_seq + (live ? i : 0);
+  a_rows[m] = row;
   out_rows[m] = live ? seq * b.rows_per_seq + i : -1;
+  if (pos_list) pos_list[m] = kv_len[seq] + b.depth[row] + 1;
 }
 
 hipError_t launch_node_rows(hipStream_t st, const BlockDev& b, int max_nodes, int32_t* a_rows,
-                            int32_t* out_rows) {
+                            int32_t* out_rows, const int32_t* kv_len, int32_t* pos_list) {
   int n = b.batch * max_nodes;
-  hipLaunchKernelGGL(k_node_rows, dim3((n + 255) / 256), dim3(256), 0, st, b, max_nodes, a_rows, out_rows);
+  hipLaunchKernelGGL(k_node_rows, dim3((n + 255) / 256), dim3(256), 0, st, b, max_nodes, a_rows, out_rows, kv_len,
+                     pos_list);
+  return hipGetLastError();
+}
+
+__global__ void k_row_positions(BlockDev b, const int32_t* __restrict__ kv_len, int32_t* pos_rows) {
+  int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= b.batch * b.rows_per_seq) return;
+  pos_rows[row] = kv_len[row / b.rows_per_seq] + b.depth[row] + 1;
+}
+
+hipError_t launch_row_positions(hipStream_t st, const BlockDev& b, const int32_t* kv_len, int32_t* pos_rows) {
+  int n = b.batch * b.rows_per_seq;
+  hipLaunchKernelGGL(k_row_positions, dim3((n + 255) / 256), dim3(256), 0, st, b, kv_len, pos_rows);
   return hipGetLastError();
 }
 

@@ -40,7 +40,8 @@ template <int MT, int NB, int D, bool TILED, int WM, int EPI>   // D even; WM wa
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
-                                               int m_tiles, int n_tiles, int a_ld, float* __restrict__ out2) {
+                                               int m_tiles, int n_tiles, int a_ld, float* __restrict__ out2,
+                                               const int32_t* __restrict__ draw_pos, uint32_t seed) {
   // XCD-aware logical id: consecutive hardware ids go to different XCDs, so give each XCD a
   // contiguous range of tiles (tiles sharing weight rows then share an L2).
   const int total = m_tiles * n_tiles * splits;
@@ -205,10 +206,14 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
       for (int v = 0; v < 16; ++v) {
         float best = -INFINITY;
         int bi = 0x7fffffff;
+        // sample matching: the row draws its next token, arg-max of logit + Gumbel noise
+        const uint32_t pos =
+            draw_pos ? (uint32_t)draw_pos[min(m0 + i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3), M - 1)] : 0u;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
           const int n = n0 + nb * 32 + lr;
-          const float x = acc[i][nb][v];
+          float x = acc[i][nb][v];
+          if (draw_pos) x += gumbel_noise(seed, pos, (uint32_t)n);
           if (n0 + nb * 32 < N && (x > best || (x == best && n < bi))) { best = x; bi = n; }
         }
 #pragma unroll
@@ -292,9 +297,11 @@ template <int MT, int NB, int D, bool TILED, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                    const bf16_t* __restrict__ W, float* __restrict__ out, int M,
                                                    int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
-                                                   float* __restrict__ out2) {
+                                                   float* __restrict__ out2, const int32_t* __restrict__ draw_pos,
+                                                   uint32_t seed) {
   extern __shared__ __align__(16) unsigned char lds[];   // 2 buffers of MT*32 rows * A_ROW_BYTES
-  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld, out2);
+  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld, out2,
+                                           draw_pos, seed);
 }
 
 template <int MT, int NB, int D, bool TILED, int EPI>
@@ -303,7 +310,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
     float* __restrict__ out2) {
   extern __shared__ __align__(16) unsigned char lds[];
-  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld, out2);
+  gemm_bf16_body<MT, NB, D, TILED, 1, EPI>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld, out2,
+                                           nullptr, 0u);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -370,7 +378,8 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
 
 template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), int EPI = 0>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
-                       int N, int K, const GemmPlan& p, int a_ld = 0, float* out2 = nullptr) {
+                       int N, int K, const GemmPlan& p, int a_ld = 0, float* out2 = nullptr,
+                       const int32_t* draw_pos = nullptr, uint32_t seed = 0) {
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
@@ -380,7 +389,7 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
                        a_ld, out2);
   else
     hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
-                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2);
+                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2, draw_pos, seed);
   return hipGetLastError();
 }
 
@@ -460,15 +469,18 @@ size_t gemm_argmax_scratch_floats(int M, int N) { return (size_t)((N + 127) / 12
 
 hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
                               int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld,
-                              float* logits_out, const int32_t* arg_rows, int n_arg) {
+                              float* logits_out, const int32_t* arg_rows, int n_arg, const int32_t* draw_pos,
+                              uint32_t seed) {
   GemmPlan p = gemm_plan(ESP_BF16, M, N, K);
   hipError_t e = hipErrorInvalidValue;
   // without logits_out: pairs only (the logits are never written); with it: the fp32 logits of all M
   // rows as well
 #define ESP_AMAX_CASE(MT_)                                                                                     \
   case MT_:                                                                                                    \
-    e = logits_out ? launch_bf16<MT_, 1, true, 4, 3>(st, A, a_rows, W, logits_out, M, N, K, p, a_ld, scratch)  \
-                   : launch_bf16<MT_, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld);             \
+    e = logits_out ? launch_bf16<MT_, 1, true, 4, 3>(st, A, a_rows, W, logits_out, M, N, K, p, a_ld, scratch,  \
+                                                     draw_pos, seed)                                           \
+                   : launch_bf16<MT_, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld, nullptr,     \
+                                                     draw_pos, seed);                                          \
     break;
   switch (p.mt) {
     ESP_AMAX_CASE(1)

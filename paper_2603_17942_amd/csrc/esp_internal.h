@@ -34,6 +34,18 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// ---- sample matching (temperature 1): counter-based Gumbel noise ---------------------------------
+// u in (0,1) from a 32-bit multiply-xorshift mix (MurmurHash3 finaliser family) of (seed, position,
+// token id), top 23 bits centred in their cell (exact in fp32); g = -ln(-ln u) is standard Gumbel, and
+// arg-max over the vocabulary of logit + g is a draw from softmax(logits).  `position` is the absolute
+// position of the token being drawn, so a draw does not depend on how its position is reached.
+__device__ __forceinline__ float gumbel_noise(uint32_t seed, uint32_t position, uint32_t id) {
+  uint32_t x = id * 0x9E3779B1u + position * 0x85EBCA77u + seed * 0xC2B2AE3Du;
+  x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+  const float u = ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f);
+  return -logf(-logf(u));
+}
+
 // ---- KV cache addressing (see esp_kv in esp.h) --------------------------------------------
 // Per (layer, kv head) plane of capacity*hd elements, in blocks of 32 slots stored in the order
 // the matrix cores consume them (v_mfma_f32_32x32x16 A operands, 64 lanes x 8 elements each):
@@ -79,7 +91,8 @@ size_t gemm_argmax_scratch_floats(int M, int N);
 // logits_out != NULL: also writes the fp32 logits [M][N]; arg-max only for the n_arg rows arg_rows[i].
 hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, int M, int N,
                               int K, float* scratch, int32_t* out, const int32_t* out_index, int a_ld,
-                              float* logits_out, const int32_t* arg_rows, int n_arg);
+                              float* logits_out, const int32_t* arg_rows, int n_arg,
+                              const int32_t* draw_pos = nullptr, uint32_t seed = 0);   // draw_pos: per GEMM row
 
 // ---- elementwise / glue (esp_elementwise.hip) ----------------------------------------------
 struct BlockDev {   // device-side view of esp_block + esp_kv scalars, passed by value
@@ -104,9 +117,15 @@ hipError_t launch_qkv_post(hipStream_t st, int dtype, const BlockDev& b, const K
                            const float* part, int splits, int M, int hq, int hkv, int hd, int qk_norm,
                            const void* qg, const void* kg, float eps, const float* rope_tab, void* q_out);
 hipError_t launch_swiglu(hipStream_t st, int dtype, const float* part, int splits, int M, int dff, void* act);
+// draw_pos (nullable): sample instead of arg-max -- entry m draws position draw_pos[m] with `seed`
 hipError_t launch_argmax(hipStream_t st, const float* logits, size_t row_stride, const int32_t* row_map,
-                         int n_rows_out, int vocab, int32_t* out, const int32_t* out_index);
-hipError_t launch_node_rows(hipStream_t st, const BlockDev& b, int max_nodes, int32_t* a_rows, int32_t* out_rows);
+                         int n_rows_out, int vocab, int32_t* out, const int32_t* out_index,
+                         const int32_t* draw_pos = nullptr, uint32_t seed = 0);
+// pos_list (nullable): position of the token that follows node-list entry m (len + depth + 1)
+hipError_t launch_node_rows(hipStream_t st, const BlockDev& b, int max_nodes, int32_t* a_rows, int32_t* out_rows,
+                            const int32_t* kv_len = nullptr, int32_t* pos_list = nullptr);
+// pos_rows[row] = len[seq] + depth[row] + 1 for every block row
+hipError_t launch_row_positions(hipStream_t st, const BlockDev& b, const int32_t* kv_len, int32_t* pos_rows);
 hipError_t launch_kv_copy(hipStream_t st, int dtype, const KvDev& kv, int layer, int n_kv, int hd,
                           int seq_base, int first_slot, int n_slots, void* k_rows, void* v_rows, int to_cache);
 hipError_t launch_mask_mean(hipStream_t st, int dtype, const void* embed, const int32_t* tokens, int n, int k,
@@ -165,6 +184,9 @@ struct esp_ctx {
   float* attn_part;  // attention split partials
   // logits of all block rows left in `logits` by the last esp_tree_forward (bf16, <= 128 rows), for
   // esp_mask_topk on the same hidden states: the hidden buffer they came from and the row count
+  int sample_on = 0;            // sample matching instead of greedy verification
+  uint32_t sample_seed = 0;
+  int32_t *idx_c, *idx_d;       // draw positions per block row / per node-list entry
   const void* lm_cache_hidden = nullptr;
   int lm_cache_rows = 0;
   float* rope_tab;   // [Mmax][hd/2][2] cos, sin

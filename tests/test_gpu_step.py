@@ -333,3 +333,107 @@ def test_hip_graph_replay_matches_eager_steps(B):
     assert graph[0] == eager[0]
     assert graph[1] == eager[1]
     assert np.array_equal(graph[2], eager[2]) and np.array_equal(graph[3], eager[3])
+
+
+# ---------------------------------------------------------------------------------------------
+# sample matching (temperature 1)
+# ---------------------------------------------------------------------------------------------
+def gpu_sampled_ar(B, decode, shape, w, prompt, n_new, seed, cap=512):
+    """One-token-at-a-time sampling on the GPU path: a tree of the root alone, sampling on."""
+    params = B.tree_params(1, 1, 1, 1, True, False, B.LAYOUT_ROOT_CHAIN)
+    dec = decode.EspDecoder(shape, w, params, 1, [cap], prefill_chunk=64)
+    dec.eng.set_sampling(True, seed)
+    out = dec.generate([prompt], n_new)[0]
+    assert dec.eng.device_status() == 0
+    dec.eng.close()
+    return out
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_config1_sampled_loop_is_lossless_and_matches_oracle(B, tiny_setup, layout):
+    """Sample matching on the tiny fp32 model: (a) the GPU's one-token-at-a-time sampling draws the
+    oracle's tokens (same counter-based noise); (b) the GPU ESP loop with sampling on emits that
+    sequence token for token and agrees with the oracle's sampled ESP loop step by step, with
+    planted continuations so that acceptance occurs."""
+    decode, shape, w, prompt, m = tiny_setup
+    n_new, k, K, kp, Bn, seed = 24, 3, 4, 6, 15, 1234
+    ref_cpu = O.greedy_generate(m, prompt, n_new + 8, "f32", sample_seed=seed)
+    ref_gpu = gpu_sampled_ar(B, decode, shape, w, prompt, n_new + 8, seed)
+    assert ref_gpu == ref_cpu
+    assert ref_cpu != O.greedy_generate(m, prompt, n_new + 8, "f32")
+    params = B.tree_params(Bn, k, K, 1, True, False, layout)
+    dec = make_decoder(B, decode, shape, w, params, kp)
+    dec.eng.set_sampling(True, seed)
+    dec.prefill([prompt])
+    st = oracle_state_after_prefill(m, prompt, k, "f32")
+    op = O.TreeParams(B=Bn, k=k, K=K, expand_width=1)
+    out, step, accepted = [], 0, 0
+    while len(out) < n_new:
+        res = O.esp_step(m, st, op, layout, kp, "f32", sample_seed=seed)
+        dec.step()
+        got = dec.emitted()[0]
+        assert got == res.emitted, (step, got, res.emitted)
+        out.extend(got)
+        accepted += len(got) - 1
+        step += 1
+        if step % 2 == 1:
+            tok, parent = planted(shape.vocab, ref_gpu[len(out):], 3, 300 + step)
+            tok[0] = out[-1]
+            dec.set_tree([tok], [parent])
+            st.tok, st.parent = np.asarray(tok), np.asarray(parent)
+    assert dec.eng.device_status() == 0
+    assert out[:n_new] == ref_gpu[:n_new]
+    assert accepted >= 6
+    dec.eng.close()
+
+
+@pytest.mark.parametrize("n_nodes,k", [(12, 2), (40, 4)])
+def test_bf16_sampled_loop_is_lossless_up_to_near_ties(B, n_nodes, k):
+    """bf16 path (noise in the LM-head GEMM's arg-max epilogue; 36 rows = one pass over the LM head
+    for all rows, 200 rows = gathered tree rows): the ESP loop with sampling on reproduces the same
+    path's one-token-at-a-time sampling; a token may differ only where the margin of the noisy
+    arg-max is inside the bf16 band."""
+    from paper_2603_17942_amd import decode
+    shape = small_shape(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=1280, vocab=4096, n_layers=2,
+                        dtype="bf16", rope_theta=5.0e5)
+    w = synth.make_weights(shape, seed=18)
+    prompt = synth.make_prompt(100, shape.vocab, seed=19).tolist()
+    n_new, seed = 20, 77
+    ref = gpu_sampled_ar(B, decode, shape, w, prompt, n_new + 6, seed, cap=1024)
+    params = B.tree_params(n_nodes, k, 4, 0, True, False, B.LAYOUT_PER_NODE)
+    dec = decode.EspDecoder(shape, w, params, 6, [1024], prefill_chunk=64)
+    dec.eng.set_sampling(True, seed)
+    dec.prefill([prompt])
+    M = dec.rows_per_seq
+    # a second decoder on the same engine runs the debug path (logits of all rows written, noisy
+    # arg-max taken by the stand-alone kernel); `dec` runs the fused epilogues
+    dbg = decode.EspDecoder(shape, w, params, 6, [1024], prefill_chunk=64, engine=dec.eng)
+    dbg.prefill([prompt])
+    dbg.logits_dbg = torch.zeros((M, shape.vocab), dtype=torch.float32, device="cuda")
+    out, step, accepted = [], 0, 0
+    while len(out) < n_new:
+        L0 = int(dec.kv.len[0])
+        depth = dec.cur.depth[:M].tolist()
+        dbg.step()
+        dec.step()
+        got = dec.emitted()[0]
+        assert got == dbg.emitted()[0], step            # fused and stand-alone draws agree
+        want = ref[len(out):len(out) + len(got)]
+        if got != want:
+            lg = dbg.logits_dbg.cpu().numpy()
+            rows = dec.accepted_row[0, :len(got)].tolist()
+            noisy = [lg[r].astype(np.float64) -
+                     np.log(-np.log(O.counter_uniform(seed, L0 + depth[r] + 1, np.arange(shape.vocab)))) for r in rows]
+            assert any(not decisive(x, 2e-2) for x in noisy), (step, got, want)
+            break
+        out.extend(got)
+        accepted += len(got) - 1
+        step += 1
+        if step % 2 == 1:
+            tok, parent = planted(shape.vocab, ref[len(out):], 2, 400 + step)
+            tok[0] = out[-1]
+            dec.set_tree([tok], [parent])
+            dbg.set_tree([tok], [parent])
+    assert dec.eng.device_status() == 0
+    assert len(out) >= 8 and accepted >= 2
+    dec.eng.close()
