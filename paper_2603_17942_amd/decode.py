@@ -126,6 +126,9 @@ class EspDecoder:
         """Tokens emitted by the last step, per sequence (synchronises)."""
         ne = self.n_emit.cpu().tolist()
         et = self.emit_tok.cpu().tolist()
+        # the host is in step with the device here: replace the running upper bound of the cache
+        # length (k+1 per step) by the true value
+        self.kv.len_bound = int(self.kv.len.max())
         return [et[b][:ne[b]] for b in range(self.batch)]
 
     def generate(self, prompts, n_new: int) -> List[List[int]]:

@@ -243,3 +243,71 @@ def test_batched_step_against_oracle(B):
             assert int(dec.kv.len[b]) == st.cache_len
             assert int(dec.cur.n_nodes[b]) == len(res.next_tok)
     dec.eng.close()
+
+
+def test_qwen3_shape_256_token_generation_loop(B):
+    """configs[2] at full depth: Qwen3-8B shape (36 layers, QK-norm, vocabulary 151936), cache of
+    4096 prompt tokens (GPU prefill), k = 5 mask tokens, Top-K 10, trees of 96 nodes (576 rows per
+    step), mask EMA on: 256 generated tokens.  The oracle cannot run this size; losslessness is
+    checked against the same kernels' one-token-at-a-time decoding, kept in step with the ESP
+    loop (it is fed the tokens the loop emits): every emitted token must be the greedy token of
+    its prefix, or within the bf16 band of it (the two paths sum attention over a different key
+    order, and with random weights over 151936 tokens near-ties are common).  The cache length
+    always equals prompt + emitted tokens, and every third step the tree carries the true
+    continuation (three tokens of look-ahead by the reference), so that multi-token acceptance
+    and the KV commit are exercised at this size."""
+    from paper_2603_17942_amd import decode
+    shape = synth.SHAPES["qwen3_8b"]
+    print("qwen3 loop: weights", flush=True)
+    w = synth.make_weights(shape, seed=1, device="cuda")
+    L0, n_new, k, K, kp, nodes = 4096, 256, 5, 10, 12, 96
+    prompt = synth.make_prompt(L0 + 1, shape.vocab, seed=2).tolist()
+    decode.EspDecoder.default_max_rows = nodes * (k + 1)
+    ar = decode.EspDecoder(shape, w, B.tree_params(1, 1, 1, 1, True, False, B.LAYOUT_ROOT_CHAIN), 1,
+                           [L0 + n_new + 1024], prefill_chunk=256)
+    eng = ar.eng
+    print("qwen3 loop: prefill", flush=True)
+    ar.prefill([prompt])
+    ar.logits_dbg = torch.zeros((ar.rows_per_seq, shape.vocab), dtype=torch.float32, device="cuda")
+    params = B.tree_params(nodes, k, K, 0, True, False, B.LAYOUT_PER_NODE)
+    dec = decode.EspDecoder(shape, w, params, kp, [L0 + n_new + 1024], prefill_chunk=256, ema_lambda=0.1, engine=eng)
+    dec.prefill([prompt])
+
+    def ar_feed(root_tok):
+        """One reference forward with `root_tok` as the last token; returns the logits of its successor."""
+        ar.set_tree([[int(root_tok)]], [[-1]])
+        ar.step()
+        return ar.logits_dbg[0]
+
+    print("qwen3 loop: ESP loop", flush=True)
+    out, step, accepted, exact, last = [], 0, 0, 0, prompt[-1]
+    while len(out) < n_new:
+        dec.step()
+        got = dec.emitted()[0]
+        assert 1 <= len(got) <= k + 1
+        assert int(dec.kv.len[0]) == L0 + len(out) + len(got)
+        for g in got:                                   # the reference follows, token by token
+            lg = ar_feed(last)
+            top = float(lg.max())
+            exact += int(int(lg.argmax()) == g)
+            assert float(lg[g]) >= top - 2 * TOL * float(lg.abs().max()), (len(out), g, int(lg.argmax()))
+            out.append(g)
+            last = g
+        accepted += len(got) - 1
+        step += 1
+        if step % 3 == 1:
+            # three tokens of look-ahead by the reference, then rewind it; plant them as a chain
+            L_sync = int(ar.kv.len[0])
+            cont, t = [], last
+            for _ in range(3):
+                t = int(ar_feed(t).argmax())
+                cont.append(t)
+            ar.kv.set_len([L_sync])
+            dec.set_tree([[last] + cont], [[-1, 0, 1, 2]])
+    assert eng.device_status() == 0
+    print(f"qwen3 loop: {step} steps, {len(out)} tokens, {accepted} accepted draft tokens, "
+          f"{exact} of {len(out)} tokens are the reference's arg-max exactly", flush=True)
+    assert exact >= 0.85 * len(out)          # the rest sit inside the band (asserted above, token by token)
+    assert accepted >= 60                # about a third of the steps carry three true tokens
+    decode.EspDecoder.default_max_rows = 0
+    eng.close()
