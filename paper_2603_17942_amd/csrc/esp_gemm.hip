@@ -8,6 +8,10 @@
 //    LDS hop.  Tiles are ordered chunk-major ([chunk][row block]): at any moment the waves of the
 //    whole grid, which advance through the chunks together, read one contiguous window of HBM.  Inside a chunk the k index is permuted identically for both operands (lane group g,
 //    step s holds k = 32 g + 8 s + 0..7), which leaves the dot product unchanged.
+//  * Large tiles (>= 8 MFMA tiles per wave, one wave per SIMD; k_gemm_bf16_ring): both operands go
+//    global -> LDS directly (global_load_lds_dwordx4, no register hop) into a ring of three chunk
+//    stages that fills all but 4 KB of the CU's LDS; the loads of chunk c+2 are issued between the
+//    MFMA groups of chunk c.  Smaller tiles keep the operands in register rings:
 //  * A register ring keeps D chunks of weights in flight per wave.  The activations of a chunk (L2
 //    resident, shared by the four waves through LDS) ride in a ring of the same depth and are issued
 //    together with the weights of the same chunk: loads retire in order, so waiting for the
@@ -34,9 +38,23 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
+// One 16-byte piece per lane from global memory straight into LDS (no register hop): the lane
+// supplies its own global address, the wave's 64 pieces land at lds_addr + 16 * lane.  Issued as
+// text so that the compiler's wait-count bookkeeping knows nothing of it: the ring below counts
+// its own loads (they retire in order) and would otherwise be drained before every LDS read.
+__device__ __forceinline__ void load_to_lds16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N_YOUNGER>
+__device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_YOUNGER) : "memory");
+}
+
 // EPI: epilogue -- 0 fp32 tile out, 1 per-row arg-max over the workgroup's columns (pairs to out),
 // 2 SwiGLU of interleaved gate/up column blocks to bf16, 3 fp32 tile to out and arg-max pairs to out2
-template <int MT, int NB, int D, bool TILED, int WM, int EPI>   // D even; WM wave groups along M
+// RING > 0 (packed weights only): both operands ride a ring of RING chunk stages in LDS, filled
+// by load_to_lds16 two chunks ahead of their use; RING == 0: register rings of depth D.
+template <int MT, int NB, int D, bool TILED, int WM, int EPI, int RING = 0>   // D even; WM wave groups along M
 __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t* __restrict__ A,
                                                const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
                                                float* __restrict__ out, int M, int N, int K, int splits,
@@ -64,6 +82,111 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   const int c_begin = z * cps;
   const int c_end = min(chunks, c_begin + cps);
 
+  f32x16_t acc[MT][NB];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  if constexpr (RING > 0) {
+    static_assert(TILED && WM == 1, "the ring path streams packed weights");
+    // A stage holds chunk c of both operands, 1 KB per wave-load:
+    //   activations [MT row tiles][32 rows][128 bytes], then weights [4 waves][NB column blocks]
+    //   [4 steps] in MFMA fragment order (a linear copy of the packed layout).
+    // An activation wave-load covers 8 rows of 128 bytes (8 lanes per row, so the global side stays
+    // coalesced); within a row the eight 16-byte pieces are stored XOR-swizzled by the row index
+    // (the lane fetches piece col ^ swz(row) for slot col), which makes the fragment reads -- lane
+    // (r, g) wants piece 4 g + s of row r -- free of bank conflicts without padding.  Wave w brings
+    // in the activation quarter-tiles w, w + 4, ... and its own weights.
+    constexpr int A_STAGE = MT * 4096, STAGE = A_STAGE + 4 * NB * 4096;
+    constexpr int LOADS = MT + 4 * NB;                    // per wave and chunk
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    auto swz = [](int r) { return (r & 7) ^ ((r >> 3) & 1); };
+    const bf16_t* apr[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+      const int pr = wave_u + 4 * j;                      // row tile pr / 4, rows 8 (pr % 4) .. + 7 of it
+      const int rt = 8 * (pr & 3) + (lane >> 3);
+      int m = min(mt0 + (pr >> 2) * 32 + rt, M - 1);
+      if (a_rows) m = max(a_rows[m], 0);
+      apr[j] = A + (a_ld > 0 ? (size_t)m * KC : (size_t)m * K) + 8 * ((lane & 7) ^ swz(rt));
+    }
+    int a_rd[4];                                          // this lane's fragment of step s inside a row tile
+#pragma unroll
+    for (int st = 0; st < 4; ++st) a_rd[st] = lr * 128 + (((4 * lg + st) ^ swz(lr)) << 4);
+    const size_t a_cs = a_ld > 0 ? (size_t)a_ld * KC : (size_t)KC;
+    const u32x4_t* wpr[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int blk = min((n0 + nb * 32) >> 5, (N >> 5) - 1);   // clamped: computed, never stored
+      wpr[nb] = reinterpret_cast<const u32x4_t*>(W) + (size_t)blk * 256 + lane;
+    }
+    const size_t W_CHUNK = (size_t)(N >> 5) * 256;
+    // load l of a chunk: l < MT activation quarter-tiles, then the weights (column block, step)
+    auto issue_one = [&](int l, int c, uint32_t sb) {
+      if (l < MT) {
+        load_to_lds16(apr[l] + (size_t)c * a_cs, sb + (wave_u + 4 * l) * 1024);
+      } else {
+        const int nb = (l - MT) >> 2, st = (l - MT) & 3;
+        load_to_lds16(wpr[nb] + (size_t)c * W_CHUNK + st * 64, sb + A_STAGE + (wave_u * NB + nb) * 4096 + st * 1024);
+      }
+    };
+    // One chunk of matrix work from `stage`; with `pre` the loads of chunk c_pre go out between
+    // the MFMA groups, spread evenly.  (Issued as one burst they would hold the wave at the
+    // memory pipeline's address queue -- the four waves' loads take about as long to drain as
+    // the chunk's MFMAs take to run -- and the matrix cores would idle meanwhile.)
+    auto chunk = [&](int stage, bool pre, int c_pre, int stage_pre) {
+      const uint32_t sb = lds0 + stage_pre * STAGE;
+      const unsigned char* sa = lds + stage * STAGE;
+      const unsigned char* sw = sa + A_STAGE + wave_u * NB * 4096 + lane * 16;
+      bf16x8_t af[2][MT], wf[2][NB];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(sa + i * 4096 + a_rd[0]);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) wf[0][nb] = *reinterpret_cast<const bf16x8_t*>(sw + nb * 4096);
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          if (st < 3) {
+            af[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(sa + i * 4096 + a_rd[st + 1]);
+            if (i < NB) wf[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(sw + i * 4096 + (st + 1) * 1024);
+          }
+          {   // LOADS loads spread evenly over the 4 MT groups
+            constexpr int SLOTS = 4 * MT;
+            const int q = st * MT + i;
+            if ((q * LOADS) / SLOTS != ((q + 1) * LOADS) / SLOTS && pre) issue_one((q * LOADS) / SLOTS, c_pre, sb);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[i][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][i], wf[st & 1][nb], acc[i][nb], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
+    static_assert(LOADS <= 4 * MT, "one load per MFMA group");
+    const int nc = c_end - c_begin;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      if (u < nc)
+#pragma unroll
+        for (int l = 0; l < LOADS; ++l) issue_one(l, c_begin + u, lds0 + u * STAGE);
+    int stage = 0;
+    for (int c = 0; c < nc; ++c) {
+      // chunk c has landed (this wave's part; the barrier covers the other waves'), chunk c + 1
+      // stays in flight
+      if (c + 1 < nc) wait_loads_but<LOADS>();
+      else wait_loads_but<0>();
+      __syncthreads();                                    // also: everyone is done with chunk c - 1's stage
+      chunk(stage, c + 2 < nc, c_begin + c + 2, stage >= RING - 2 ? stage + 2 - RING : stage + 2);
+      stage = stage + 1 == RING ? 0 : stage + 1;
+    }
+    __syncthreads();                                      // the epilogues reuse the LDS
+  } else {
   // weight pointers (clamped: out-of-range column blocks are computed but never stored)
   const u32x4_t* wp[NB];
 #pragma unroll
@@ -96,14 +219,6 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
   // of a chunk on the same L2 channel when all workgroups walk the chunks in step)
   const size_t a_cs = a_ld > 0 ? (size_t)a_ld * KC : (size_t)KC;
   constexpr int A_BUF = WM * MT * 32 * A_ROW_BYTES;
-
-  f32x16_t acc[MT][NB];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   u32x4_t wreg[D][NB][4];
   u32x4_t areg[D][MT];
@@ -148,6 +263,15 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         for (int i = 0; i < MT; ++i) {
           if (s < 3)
             af[(s + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(abase + i * 32 * A_ROW_BYTES + 16 * (s + 1));
+          {
+            // refill of ring slot u with chunk c+D, one load per MFMA group (a burst after the
+            // MFMAs would hold the wave at the memory pipeline's address queue while the matrix
+            // cores idle): the activation registers are free (stored to LDS a chunk ago), the
+            // weight registers of step s-1 were consumed by the previous step
+            const int cc = min(c + D, c_last);
+            if (s == 0) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * a_cs);
+            else if (i < NB) wreg[u][i][s - 1] = wp[i][(size_t)cc * W_CHUNK + (s - 1) * W_STEP];
+          }
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
@@ -162,20 +286,16 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
       for (int i = 0; i < MT; ++i)
         *reinterpret_cast<u32x4_t*>(lds + (buf ^ 1) * A_BUF + a_lds[i]) =
             c + 1 < c_end ? areg[(u + 1) % D][i] : zero4;   // zeroed at use, not at load
-      // refill ring slot u with chunk c+D
+      // the last step's weight registers of ring slot u
       {
-        const int cn = c + D;
-        const int cc = min(cn, c_last);
+        const int cc = min(c + D, c_last);
 #pragma unroll
-        for (int i = 0; i < MT; ++i) areg[u][i] = *reinterpret_cast<const u32x4_t*>(ap[i] + (size_t)cc * a_cs);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) wreg[u][nb][s] = wp[nb][(size_t)cc * W_CHUNK + s * W_STEP];
+        for (int nb = 0; nb < NB; ++nb) wreg[u][nb][3] = wp[nb][(size_t)cc * W_CHUNK + 3 * W_STEP];
       }
       __syncthreads();
     }
   }
+  }   // register-ring path
 
   // epilogue: lane holds column n, rows 8*(v/4) + 4*lg + v%4 of each 32x32 tile
   if (EPI == 0 || EPI == 3) {
@@ -314,6 +434,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                                            nullptr, 0u);
 }
 
+// Large tile with the LDS ring: one workgroup per CU owns (almost) the whole LDS.
+constexpr int RING_STAGES = 3;
+template <int MT, int NB>
+constexpr size_t ring_lds_bytes() { return (size_t)RING_STAGES * (MT * 4096 + 4 * NB * 4096); }
+
+template <int MT, int NB, int EPI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_ring(
+    const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
+    float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
+    float* __restrict__ out2) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  gemm_bf16_body<MT, NB, 2, true, 1, EPI, RING_STAGES>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld,
+                                                      out2, nullptr, 0u);
+}
+
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
 __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, const int32_t* __restrict__ a_rows,
                                                   const float* __restrict__ W, float* __restrict__ out, int M,
@@ -383,7 +518,16 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
   int total = p.m_tiles * p.n_tiles * p.splits;
   int per_xcd = (total + 7) / 8;
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
-  if constexpr (MT * NB >= 8)
+  if constexpr (MT * NB >= 8 && TILED) {
+    auto kern = k_gemm_bf16_ring<MT, NB, EPI>;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)ring_lds_bytes<MT, NB>());
+    if (attr != hipSuccess) return attr;
+    const size_t ring_bytes = ring_lds_bytes<MT, NB>();
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), ring_bytes, st, (const bf16_t*)A, a_rows,
+                       (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2);
+  } else if constexpr (MT * NB >= 8)
     hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st,
                        (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles,
                        a_ld, out2);
