@@ -30,7 +30,7 @@ random-weight workloads are pinned only through the library decoder.
 from __future__ import annotations
 
 import dataclasses
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -474,6 +474,36 @@ def mask_mean_init(model: Model, prompt: Sequence[int], k: int) -> np.ndarray:
         m += as_f64(emb[int(t)])
     m /= len(prompt)
     return np.tile(m[None, :], (k, 1))
+
+
+def mask_last_k_init(model: Model, prompt: Sequence[int], k: int) -> np.ndarray:
+    """Hard initialisation (Sec. 4, mask-design ablation, variant a): the embeddings of the last
+    k prompt tokens.  The printed index would skip those very tokens, so the words are followed:
+    mask i is the prompt token k - i places before the end, m_i = e_{t-k+i}, in prompt order."""
+    if len(prompt) < k:
+        raise ValueError("prompt shorter than k")
+    emb = model.weights["embed"]
+    return np.stack([as_f64(emb[int(t)]) for t in prompt[len(prompt) - k:]], axis=0)
+
+
+def embed_table_stats(model: Model) -> Tuple[np.ndarray, float]:
+    """Gaussian fit to the embedding table (Sec. 4, variant b; App. on masks outside the embedding
+    distribution): mu = mean over the V rows (one value per dimension), sigma = one scalar, the
+    root mean square deviation of all V * d entries from their dimension's mean (the paper's
+    covariance is sigma^2 I)."""
+    emb = as_f64(model.weights["embed"])
+    mu = emb.mean(axis=0)
+    sigma = float(np.sqrt(np.mean((emb - mu[None, :]) ** 2)))
+    return mu, sigma
+
+
+def mask_gaussian_init(model: Model, k: int, z: np.ndarray | None, shift: float = 0.0) -> np.ndarray:
+    """m_i = mu + (shift + z_i) sigma.  z: [k, d] standard normal draws handed in by the caller
+    (variant b, shift 0), or None with shift 5 or 10 for the out-of-distribution rows of the
+    appendix table."""
+    mu, sigma = embed_table_stats(model)
+    zz = np.zeros((k, model.d_model), dtype=F64) if z is None else as_f64(z)
+    return mu[None, :] + (shift + zz) * sigma
 
 
 def mask_ema_update(mask_embed: np.ndarray, token_embed: np.ndarray, lam: float) -> np.ndarray:

@@ -239,3 +239,38 @@ def test_mask_mean_and_ema_closed_forms():
     for _ in range(5):
         cur = O.mask_ema_update(cur, e, lam)
     np.testing.assert_allclose(cur[0], e + (1 - lam) ** 5 * (want - e), atol=1e-14)
+
+
+def test_mask_last_k_and_gaussian_inits_on_tables_with_known_statistics():
+    """Sec. 4 mask-design variants a and b, and the out-of-distribution rows of the appendix table."""
+    shape = small_shape(n_layers=1)
+    w = synth.make_weights(shape, seed=32)
+    m = oracle_model(shape, w)
+    emb = m.weights["embed"]
+    # a. the last k prompt tokens, in prompt order
+    lk = O.mask_last_k_init(m, [3, 5, 6, 9], 2)
+    np.testing.assert_array_equal(lk[0], np.asarray(emb[6], np.float64))
+    np.testing.assert_array_equal(lk[1], np.asarray(emb[9], np.float64))
+    with pytest.raises(ValueError):
+        O.mask_last_k_init(m, [3], 2)
+    # b. a table built to have mean a_d in dimension d and every entry exactly b away from it
+    V, d = emb.shape
+    a = np.linspace(-0.5, 0.75, d)
+    sign = np.where(np.arange(V - V % 2) % 2 == 0, 1.0, -1.0)  # an even number of rows: the signs cancel
+    m.weights["embed"] = a[None, :] + 0.125 * sign[:, None]
+    mu, sigma = O.embed_table_stats(m)
+    np.testing.assert_allclose(mu, a, atol=1e-15)
+    assert abs(sigma - 0.125) < 1e-15
+    np.testing.assert_allclose(O.mask_gaussian_init(m, 3, None, 5.0), np.tile(a + 0.625, (3, 1)), atol=1e-14)
+    np.testing.assert_allclose(O.mask_gaussian_init(m, 3, None, 10.0), np.tile(a + 1.25, (3, 1)), atol=1e-14)
+    z = np.random.default_rng(5).standard_normal((3, d))
+    g = O.mask_gaussian_init(m, 3, z)
+    np.testing.assert_allclose((g - a[None, :]) / 0.125, z, atol=1e-12)
+    # the seeded N(0, 0.02^2) table: the fit recovers the generator's parameters, and masks drawn
+    # from the fit have the table's own first two moments
+    m.weights["embed"] = emb
+    mu, sigma = O.embed_table_stats(m)
+    assert np.max(np.abs(mu)) < 5 * 0.02 / np.sqrt(V)
+    assert abs(sigma / 0.02 - 1) < 0.02
+    big = O.mask_gaussian_init(m, 64, np.random.default_rng(6).standard_normal((64, d)))
+    assert abs(big.std() / np.asarray(emb, np.float64).std() - 1) < 0.05
