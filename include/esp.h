@@ -259,6 +259,23 @@ esp_status esp_mask_mean(esp_ctx *ctx, const int32_t *tokens, int32_t n_tokens, 
 esp_status esp_mask_ema(esp_ctx *ctx, const int32_t *n_emit, const int32_t *emit_tok, float lambda,
                         int32_t k, void *mask_embed);
 
+/* The two other initialisations of the mask-design ablation (Sec. 4) and the out-of-distribution
+ * rows of the appendix table on mask initialisation.
+ * esp_mask_last_k: hard initialisation, mask i (0-based) = embed[tokens[n_tokens - k + i]], the last
+ *   k prompt tokens in prompt order (the index printed in the paper would skip exactly those
+ *   tokens; its words are followed).  EINVAL if n_tokens < k.
+ * esp_mask_gaussian: m_i = mu + (shift + z_i) sigma with the Gaussian fit of the embedding table:
+ *   mu[d_model] the mean over the vocabulary per dimension, sigma one scalar, the root mean square
+ *   deviation of all entries from their dimension's mean (two passes over the table, fp32 slab
+ *   sums added in fp64).  z: device fp32 [k, d_model], the caller's standard normal draws (the
+ *   library draws nothing), or NULL for z = 0; shift 0 gives the paper's "Sample" variant, z NULL
+ *   with shift 5 or 10 its mu + 5 sigma and mu + 10 sigma rows.  Uses the context's logits buffer
+ *   as scratch (logits kept for esp_mask_topk by the last esp_tree_forward are dropped).
+ * mask_embed: device [k, d_model] model dtype. */
+esp_status esp_mask_last_k(esp_ctx *ctx, const int32_t *tokens, int32_t n_tokens, int32_t k,
+                           void *mask_embed);
+esp_status esp_mask_gaussian(esp_ctx *ctx, const float *z, float shift, int32_t k, void *mask_embed);
+
 /* Copies plain K/V rows [n_slots][n_kv_heads][head_dim] (model dtype, device) of one layer into /
  * out of the cache layout at slots base + first_slot .. */
 esp_status esp_kv_store(esp_ctx *ctx, const esp_kv *kv, int32_t layer, int32_t seq_base,

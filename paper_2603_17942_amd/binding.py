@@ -58,7 +58,7 @@ class TreeParams(C.Structure):
 
 EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy", "esp_last_device_status",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
-           "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_kv_store", "esp_kv_load",
+           "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_mask_last_k", "esp_mask_gaussian", "esp_kv_store", "esp_kv_load",
            "esp_gemm_scratch_bytes", "esp_gemm", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
            "esp_softmax_topk", "esp_profile_enable", "esp_profile_read", "esp_pack_weight", "esp_set_sampling"]
 SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
@@ -96,6 +96,8 @@ def load_library() -> C.CDLL:
     lib.esp_block_from_tree.argtypes = [_vp, P(Block)]
     lib.esp_mask_mean.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.esp_mask_ema.argtypes = [_vp, _vp, _vp, _f32, _i32, _vp]
+    lib.esp_mask_last_k.argtypes = [_vp, _vp, _i32, _i32, _vp]
+    lib.esp_mask_gaussian.argtypes = [_vp, _vp, _f32, _i32, _vp]
     lib.esp_kv_store.argtypes = [_vp, P(Kv), _i32, _i32, _i32, _i32, _vp, _vp]
     lib.esp_kv_load.argtypes = [_vp, P(Kv), _i32, _i32, _i32, _i32, _vp, _vp]
     lib.esp_gemm_scratch_bytes.restype = C.c_size_t
@@ -327,6 +329,14 @@ class Engine:
 
     def mask_mean(self, tokens: torch.Tensor, k: int, mask_embed: torch.Tensor):
         _check(self.lib.esp_mask_mean(self.ctx, _ptr(tokens), tokens.numel(), k, _ptr(mask_embed)), "esp_mask_mean")
+
+    def mask_last_k(self, tokens: torch.Tensor, k: int, mask_embed: torch.Tensor):
+        _check(self.lib.esp_mask_last_k(self.ctx, _ptr(tokens), tokens.numel(), k, _ptr(mask_embed)),
+               "esp_mask_last_k")
+
+    def mask_gaussian(self, z: Optional[torch.Tensor], shift: float, k: int, mask_embed: torch.Tensor):
+        _check(self.lib.esp_mask_gaussian(self.ctx, _ptr(z) if z is not None else None, shift, k, _ptr(mask_embed)),
+               "esp_mask_gaussian")
 
     def mask_ema(self, n_emit, emit_tok, lam: float, k: int, mask_embed: torch.Tensor):
         _check(self.lib.esp_mask_ema(self.ctx, _ptr(n_emit), _ptr(emit_tok), lam, k, _ptr(mask_embed)),

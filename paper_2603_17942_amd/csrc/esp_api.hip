@@ -520,6 +520,26 @@ esp_status esp_mask_mean(esp_ctx* c, const int32_t* tokens, int32_t n_tokens, in
   return ESP_OK;
 }
 
+esp_status esp_mask_last_k(esp_ctx* c, const int32_t* tokens, int32_t n_tokens, int32_t k, void* mask_embed) {
+  if (!c || !tokens || !mask_embed || k < 1 || k > ESP_MAX_MASKS || n_tokens < k) return ESP_EINVAL;
+  ESP_HIP(launch_mask_last_k(c->stream, c->m.dtype, c->embed, tokens, n_tokens, k, c->m.d_model, c->m.vocab,
+                             mask_embed));
+  return ESP_OK;
+}
+
+esp_status esp_mask_gaussian(esp_ctx* c, const float* z, float shift, int32_t k, void* mask_embed) {
+  if (!c || !mask_embed || k < 1 || k > ESP_MAX_MASKS) return ESP_EINVAL;
+  // the statistics use the logits buffer as scratch: whatever esp_tree_forward left there for
+  // esp_mask_topk is gone
+  const size_t room = c->logits_rows * (size_t)c->m.vocab;
+  if (room < mask_gaussian_scratch_floats(c->m.d_model)) return ESP_ECAPACITY;
+  c->lm_cache_hidden = nullptr;
+  c->lm_cache_rows = 0;
+  ESP_HIP(launch_mask_gaussian(c->stream, c->m.dtype, c->embed, c->m.vocab, c->m.d_model, z, shift, k, c->logits, room,
+                               mask_embed));
+  return ESP_OK;
+}
+
 esp_status esp_mask_ema(esp_ctx* c, const int32_t* n_emit, const int32_t* emit_tok, float lambda, int32_t k,
                         void* mask_embed) {
   if (!c || !n_emit || !emit_tok || !mask_embed || k < 1 || k > ESP_MAX_MASKS) return ESP_EINVAL;

@@ -1,5 +1,7 @@
 // Glue kernels of the ESP decode step: block assembly, norms, rotary + KV append, SwiGLU,
 // argmax, KV copies, mask-vector init / update.  All HBM-light; one pass over [rows, width].
+#include <algorithm>
+
 #include "esp_internal.h"
 
 #define ESP_DISPATCH(dtype, ...)          \
@@ -369,6 +371,107 @@ hipError_t launch_mask_mean(hipStream_t st, int dtype, const void* embed, const 
                             int d, int vocab, void* mask_embed) {
   ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_mean<T>, dim3((d + 255) / 256), dim3(256), 0, st, (const T*)embed,
                                          tokens, n, k, d, vocab, (T*)mask_embed));
+  return hipGetLastError();
+}
+
+// Hard initialisation (Sec. 4, mask-design variant a): mask i = embedding of the prompt token
+// k - i places before the end.
+template <typename T>
+__global__ void k_mask_last_k(const T* __restrict__ embed, const int32_t* __restrict__ tokens, int n, int k, int d,
+                              int vocab, T* __restrict__ mask_embed) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d) return;
+  for (int j = 0; j < k; ++j) {
+    int id = tokens[n - k + j];
+    mask_embed[(size_t)j * d + i] = id >= 0 && id < vocab ? embed[(size_t)id * d + i] : from_f32<T>(0.f);
+  }
+}
+
+hipError_t launch_mask_last_k(hipStream_t st, int dtype, const void* embed, const int32_t* tokens, int n, int k,
+                              int d, int vocab, void* mask_embed) {
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_last_k<T>, dim3((d + 255) / 256), dim3(256), 0, st, (const T*)embed,
+                                         tokens, n, k, d, vocab, (T*)mask_embed));
+  return hipGetLastError();
+}
+
+// Gaussian fit to the embedding table (Sec. 4, variant b): mu[i] = mean over the vocabulary of
+// column i, sigma = root mean square deviation of all entries from their column's mean.  Two
+// passes over the table (mean, then squared deviations), each split into slabs of rows whose
+// fp32 partial sums are added up in fp64, in slab order.
+// MODE 0: partial[slab][i] = sum of column i over the slab; 1: sum of (x - mu[i])^2
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void k_embed_stats_partial(const T* __restrict__ embed, int vocab, int d,
+                                                             int rows_per_slab, const float* __restrict__ mu,
+                                                             float* __restrict__ partial) {
+  const int i = blockIdx.x * 256 + threadIdx.x, slab = blockIdx.y;
+  if (i >= d) return;
+  const int v0 = slab * rows_per_slab, v1 = min(vocab, v0 + rows_per_slab);
+  const float c = MODE ? mu[i] : 0.f;
+  float acc = 0.f;
+  for (int v = v0; v < v1; ++v) {
+    const float x = to_f32(embed[(size_t)v * d + i]) - c;
+    acc += MODE ? x * x : x;
+  }
+  partial[(size_t)slab * d + i] = acc;
+}
+
+__global__ __launch_bounds__(256) void k_embed_mean_final(const float* __restrict__ partial, int slabs, int d, int vocab,
+                                                          float* __restrict__ mu) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d) return;
+  double s = 0.0;
+  for (int b = 0; b < slabs; ++b) s += (double)partial[(size_t)b * d + i];
+  mu[i] = (float)(s / (double)vocab);
+}
+
+// one workgroup: sigma = sqrt(sum of all partials / (vocab * d))
+__global__ __launch_bounds__(256) void k_embed_sigma_final(const float* __restrict__ partial, int slabs, int d, int vocab,
+                                                           float* __restrict__ sigma) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < d; i += 256)
+    for (int b = 0; b < slabs; ++b) s += (double)partial[(size_t)b * d + i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) sigma[0] = (float)sqrt(red[0] / ((double)vocab * (double)d));
+}
+
+// m_j = mu + (shift + z_j) sigma; z: [k][d] standard normal draws of the caller, or null
+template <typename T>
+__global__ void k_mask_affine(const float* __restrict__ mu, const float* __restrict__ sigma,
+                              const float* __restrict__ z, float shift, int k, int d, T* __restrict__ mask_embed) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d) return;
+  const float sg = sigma[0], m = mu[i];
+  for (int j = 0; j < k; ++j)
+    mask_embed[(size_t)j * d + i] = from_f32<T>(fmaf(shift + (z ? z[(size_t)j * d + i] : 0.f), sg, m));
+}
+
+size_t mask_gaussian_scratch_floats(int d) { return (size_t)2 * d + 64; }   // least: one slab
+
+hipError_t launch_mask_gaussian(hipStream_t st, int dtype, const void* embed, int vocab, int d, const float* z,
+                                float shift, int k, float* scratch, size_t scratch_floats, void* mask_embed) {
+  // scratch: mu [d], sigma [64 (one used)], partial [slabs][d]
+  float* mu = scratch;
+  float* sigma = scratch + d;
+  float* partial = scratch + d + 64;
+  const size_t room = (scratch_floats - d - 64) / d;
+  const int slabs = (int)std::max<size_t>(1, std::min<size_t>(room, 256));
+  const int rows_per_slab = (vocab + slabs - 1) / slabs;
+  const int used = (vocab + rows_per_slab - 1) / rows_per_slab;
+  const dim3 grid((d + 255) / 256, used);
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL((k_embed_stats_partial<T, 0>), grid, dim3(256), 0, st, (const T*)embed, vocab,
+                                         d, rows_per_slab, (const float*)nullptr, partial));
+  hipLaunchKernelGGL(k_embed_mean_final, dim3((d + 255) / 256), dim3(256), 0, st, partial, used, d, vocab, mu);
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL((k_embed_stats_partial<T, 1>), grid, dim3(256), 0, st, (const T*)embed, vocab,
+                                         d, rows_per_slab, (const float*)mu, partial));
+  hipLaunchKernelGGL(k_embed_sigma_final, dim3(1), dim3(256), 0, st, partial, used, d, vocab, sigma);
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_affine<T>, dim3((d + 255) / 256), dim3(256), 0, st, mu, sigma, z, shift,
+                                         k, d, (T*)mask_embed));
   return hipGetLastError();
 }
 

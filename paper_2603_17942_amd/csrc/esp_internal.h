@@ -130,6 +130,11 @@ hipError_t launch_kv_copy(hipStream_t st, int dtype, const KvDev& kv, int layer,
                           int seq_base, int first_slot, int n_slots, void* k_rows, void* v_rows, int to_cache);
 hipError_t launch_mask_mean(hipStream_t st, int dtype, const void* embed, const int32_t* tokens, int n, int k,
                             int d, int vocab, void* mask_embed);
+hipError_t launch_mask_last_k(hipStream_t st, int dtype, const void* embed, const int32_t* tokens, int n, int k,
+                              int d, int vocab, void* mask_embed);
+size_t mask_gaussian_scratch_floats(int d);
+hipError_t launch_mask_gaussian(hipStream_t st, int dtype, const void* embed, int vocab, int d, const float* z,
+                                float shift, int k, float* scratch, size_t scratch_floats, void* mask_embed);
 hipError_t launch_mask_ema(hipStream_t st, int dtype, const void* embed, const int32_t* n_emit,
                            const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed);
 

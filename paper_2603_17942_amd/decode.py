@@ -52,6 +52,8 @@ class EspDecoder:
         self.topk_p = torch.zeros((self.batch, self.k, kp), dtype=torch.float32, device=device)
         self.n_lists = torch.zeros(self.batch, **i32)
         self.mask_embed = torch.zeros((self.k, shape.d_model), dtype=dt, device=device)
+        self.mask_init = "mean"         # "mean" | "last_k" | "gaussian" (with mask_z [k, d] fp32 or None, mask_shift)
+        self.mask_z, self.mask_shift = None, 0.0
         self.logits_dbg = None          # set to a [M, vocab] fp32 tensor to capture logits
         self.mask_logits = None         # set to a [batch, k, vocab] fp32 tensor to capture them
 
@@ -81,8 +83,15 @@ class EspDecoder:
                 done[b] += adv[b]
             self.kv.len.add_(torch.tensor(adv, dtype=torch.int32, device=self.device))
             self.kv.len_bound = max(done)
-        self.eng.mask_mean(torch.tensor([int(t) for t in prompts[0]], dtype=torch.int32, device=self.device),
-                           self.k, self.mask_embed)
+        ptok = torch.tensor([int(t) for t in prompts[0]], dtype=torch.int32, device=self.device)
+        if self.mask_init == "mean":            # Eq. 4, the paper's default
+            self.eng.mask_mean(ptok, self.k, self.mask_embed)
+        elif self.mask_init == "last_k":        # Sec. 4 variant a
+            self.eng.mask_last_k(ptok, self.k, self.mask_embed)
+        elif self.mask_init == "gaussian":      # Sec. 4 variant b; mask_z: the caller's normal draws
+            self.eng.mask_gaussian(self.mask_z, self.mask_shift, self.k, self.mask_embed)
+        else:
+            raise ValueError(f"unknown mask_init {self.mask_init!r}")
         self.cur.upload_trees([[int(p[-1])] for p in prompts], [[-1]] * self.batch)
         self.eng.block_from_tree(self.cur)
 

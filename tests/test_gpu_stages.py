@@ -374,3 +374,27 @@ def test_attn_tree_bf16_mfma(B, bf16_engine, n_nodes, k, layout, cache_lens):
     print(f"attn bf16 n={n_nodes} k={k} layout={layout} L={cache_lens}", flush=True)
     err = run_attention_case(B, shape, eng, n_nodes, k, layout, cache_lens, seed=70)
     assert err < 2e-2
+
+
+# ------------------------------------------------------------------------- mask initialisations
+@pytest.mark.parametrize("which", ["tiny", "bf16"])
+def test_mask_last_k_and_gaussian_inits(B, tiny_engine, bf16_engine, which):
+    """Sec. 4 mask-design variants a (last k prompt tokens) and b (Gaussian fit of the embedding
+    table), and the mu + 5 sigma / mu + 10 sigma rows of the appendix, against the oracle."""
+    shape, w, eng = tiny_engine if which == "tiny" else bf16_engine
+    print(f"mask inits {which}", flush=True)
+    m = oracle_model(shape, w)
+    k = 3
+    dt = torch.float32 if shape.dtype == "f32" else torch.bfloat16
+    tol = 1e-4 if shape.dtype == "f32" else 2e-2
+    out = torch.zeros((k, shape.d_model), dtype=dt, device="cuda")
+    prompt = [5, 9, 2, 7, 11]
+    eng.mask_last_k(torch.tensor(prompt, dtype=torch.int32, device="cuda"), k, out)
+    assert np.array_equal(to_np(out), O.mask_last_k_init(m, prompt, k))     # a copy of table rows: exact
+    z = synth.normal_like((k, shape.d_model), 1.0, 41, 0, "cuda", torch.float32)
+    for zz, shift in [(z, 0.0), (None, 5.0), (None, 10.0), (z, -1.5)]:
+        eng.mask_gaussian(zz, shift, k, out)
+        want = O.mask_gaussian_init(m, k, None if zz is None else zz.cpu().numpy(), shift)
+        assert rel_err_rows(to_np(out), want) <= tol
+    with pytest.raises(RuntimeError):
+        eng.mask_last_k(torch.tensor([1, 2], dtype=torch.int32, device="cuda"), 3, out)
