@@ -200,16 +200,20 @@ def test_ragged_batch_attention_sampled_rows(B):
     eng.close()
 
 
-def test_batched_step_against_oracle(B):
+@pytest.mark.parametrize("Bn,nodes", [(24, [24, 9, 17]), (48, [48, 20, 33])])
+def test_batched_step_against_oracle(B, Bn, nodes):
     """Three independent sequences of different cache lengths and tree sizes in one block: every
-    entry point handles the batch dimension (small bf16 model, full oracle comparison)."""
+    entry point handles the batch dimension (small bf16 model, full oracle comparison).  The larger
+    case has more than 128 tree rows, so the LM head runs on gathered rows through the large-tile
+    GEMM."""
     from paper_2603_17942_amd import decode
     shape = small_shape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=512, vocab=2048, n_layers=2,
                         dtype="bf16", rope_theta=5.0e5)
     w = synth.make_weights(shape, seed=28, unit_gains=False)
     m = oracle_model(shape, w)
-    k, K, kp, Bn, layout = 3, 4, 6, 24, 0
-    lens, nodes = [300, 64, 1000], [24, 9, 17]
+    k, K, kp, layout = 3, 4, 6, 0
+    lens = [300, 64, 1000]
+    print(f"batched step B={Bn} nodes={nodes}", flush=True)
     params = B.tree_params(Bn, k, K, 0, True, False, layout)
     dec = decode.EspDecoder(shape, w, params, kp, [l + 512 for l in lens], prefill_chunk=64)
     fills = []
