@@ -238,7 +238,7 @@ def stage_rooflines(B, synth, torch, shape, lm_head_packed):
                             device="cuda"))
         ms = time_gpu(torch, lambda: B.softmax_topk(lg, 10, bufs), 10, warm=2)
         byts = rows * N * 4
-        out[f"softmax_topk_rows{rows}"] = {"kernel": "k_topk_chunks + k_topk_merge", "bound": "hbm",
+        out[f"softmax_topk_rows{rows}"] = {"kernel": "k_topk_stream + k_topk_merge", "bound": "hbm",
                                            "achieved": byts / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                            "frac": byts / ms / 1e6 / HBM_PEAK_GBS, "bytes_per_launch": byts,
                                            "avg_launch_ms": ms}

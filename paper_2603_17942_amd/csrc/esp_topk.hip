@@ -12,7 +12,8 @@
 //     K'-th largest of its 64 lane maxima (at least K' logits reach that bound), which keeps the
 //     warm-up to a few insertions.
 // Pass 2 (k_topk_merge): one wave per row merges the segment statistics (online-softmax rule) and
-// runs the same filtered insertion over the segments' candidates; p = exp(v - max) / sum in fp32.
+// the segments' sorted lists (at most 64 segments, one per lane: K' rounds of a wave-wide best-head
+// search); p = exp(v - max) / sum in fp32.
 #include <algorithm>
 
 #include "esp_internal.h"
@@ -163,56 +164,53 @@ __global__ __launch_bounds__(256) void k_topk_stream(const float* __restrict__ l
   }
 }
 
-// one wave per row
+// one wave per row: the segments' lists are sorted, so lane c walks segment c's list and the wave
+// takes the best head (value desc, id asc) K' times -- a 64-way merge of sorted lists
 __global__ __launch_bounds__(256) void k_topk_merge(const float* __restrict__ scratch, int rows, int kp, int nseg,
                                                     int32_t* __restrict__ ids, float* __restrict__ probs) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const int stride = 2 + 2 * kp;
-  const float* base = scratch + (size_t)row * nseg * stride;
-  float lmax = -INFINITY;
-  for (int c = lane; c < nseg; c += 64) lmax = fmaxf(lmax, base[(size_t)c * stride]);
-  const float gmax = wave_max(lmax);
-  float lsum = 0.f;
-  for (int c = lane; c < nseg; c += 64) {
-    const float* e = base + (size_t)c * stride;
-    lsum += e[0] > -INFINITY ? e[1] * expf(e[0] - gmax) : 0.f;
-  }
-  const float tot = wave_sum(lsum);
-
-  LaneList L;
-  list_init(L);
-  const int ncand = nseg * kp;
-  float floor_bound = -INFINITY, bound = -INFINITY;
-  for (int c0 = 0; c0 < ncand; c0 += 64) {
-    const int i = c0 + lane;
-    float v = -INFINITY;
-    int id = 0x7fffffff;
-    if (i < ncand) {
-      const float* e = base + (size_t)(i / kp) * stride;
-      v = e[2 + i % kp];
-      id = reinterpret_cast<const int*>(e)[2 + kp + i % kp];
+  const float* e = scratch + ((size_t)row * nseg + lane) * stride;     // this lane's segment (nseg <= 64)
+  const bool have = lane < nseg;
+  const float smax = have ? e[0] : -INFINITY;
+  const float gmax = wave_max(smax);
+  const float tot = wave_sum(have && smax > -INFINITY ? e[1] * expf(smax - gmax) : 0.f);
+  int pos = 0;                                                          // next unread entry of the list
+  float hv = have ? e[2] : -INFINITY;
+  int hi = have ? reinterpret_cast<const int*>(e)[2 + kp] : 0x7fffffff;
+  if (hv == -INFINITY) hi = 0x7fffffff;                                 // empty slot: never wins
+  float out_v = -INFINITY;
+  int out_i = 0x7fffffff;
+  for (int j = 0; j < kp; ++j) {
+    float bv = hv;
+    int bi = hi;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, 64);
+      const int oi = __shfl_xor(bi, o, 64);
+      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
     }
-    if (c0 == 0) {
-      floor_bound = kth_largest_lane(v, kp, lane);
-      bound = floor_bound;
+    if (lane == j) { out_v = bv; out_i = bi; }
+    if (hi == bi && bi != 0x7fffffff) {                                 // ids are unique: exactly one lane advances
+      ++pos;
+      hv = pos < kp ? e[2 + pos] : -INFINITY;
+      hi = pos < kp ? reinterpret_cast<const int*>(e)[2 + kp + pos] : 0x7fffffff;
+      if (hv == -INFINITY) hi = 0x7fffffff;
     }
-    if (v == -INFINITY) id = 0x7fffffff;
-    // empty slots (-inf) never qualify: better() against the (-inf, INT_MAX) tail is false
-    offer(L, v, id, bound, floor_bound, kp, lane);
   }
   if (lane < kp) {
-    const bool any = L.id != 0x7fffffff;
-    ids[(size_t)row * kp + lane] = any ? L.id : -1;
-    probs[(size_t)row * kp + lane] = any ? expf(L.v - gmax) / tot : 0.f;
+    const bool any = out_i != 0x7fffffff;
+    ids[(size_t)row * kp + lane] = any ? out_i : -1;
+    probs[(size_t)row * kp + lane] = any ? expf(out_v - gmax) / tot : 0.f;
   }
 }
 
 // segments per row: enough independent waves to fill the chip (about 8 per CU), each at least one
 // block long
 int topk_segments(int rows, int vocab, int* seg_len) {
-  const int max_seg = (vocab + BLOCK - 1) / BLOCK;
+  const int max_seg = std::min(64, (vocab + BLOCK - 1) / BLOCK);   // the merge gives each segment a lane
   int nseg = std::max(1, std::min(max_seg, (2048 + rows - 1) / rows));
   int len = ((vocab + nseg - 1) / nseg + BLOCK - 1) / BLOCK * BLOCK;
   nseg = (vocab + len - 1) / len;
@@ -223,7 +221,7 @@ int topk_segments(int rows, int vocab, int* seg_len) {
 }  // namespace
 
 size_t softmax_topk_scratch_floats(int rows, int vocab, int kp) {
-  int max_seg = (vocab + BLOCK - 1) / BLOCK;   // upper bound of the segment count for any row count
+  int max_seg = std::min(64, (vocab + BLOCK - 1) / BLOCK);   // upper bound of the segment count for any row count
   return (size_t)rows * max_seg * (2 + 2 * kp);
 }
 
