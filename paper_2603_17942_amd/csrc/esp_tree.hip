@@ -178,6 +178,9 @@ struct TreeLds {
   int32_t expand[ESP_MAX_TREE_NODES];
   int32_t scan[256];
   int32_t n_total, n_frontier, n_expand, bad;
+  int32_t n_surv, bin1, before1, bin2;   // select_best
+  int32_t list_id[ESP_MAX_MASKS * ESP_MAX_TOPK];   // the sequence's Top-K' lists, staged once
+  float list_p[ESP_MAX_MASKS * ESP_MAX_TOPK];
 };
 
 __device__ __forceinline__ uint64_t cand_key(float p, int creation) {
@@ -202,18 +205,108 @@ __device__ void bitonic_sort(uint64_t* key, int n_pow2) {
 
 // exclusive scan of one value per thread over the 256-thread block; returns (prefix, total via *tot)
 __device__ int block_excl_scan(int v, int32_t* buf, int* tot) {
-  buf[threadIdx.x] = v;
-  __syncthreads();
-  for (int o = 1; o < 256; o <<= 1) {
-    int x = threadIdx.x >= o ? buf[threadIdx.x - o] : 0;
-    __syncthreads();
-    buf[threadIdx.x] += x;
-    __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int x = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += x;
   }
-  int incl = buf[threadIdx.x];
-  *tot = buf[255];
+  if (lane == 63) buf[wave] = incl;
   __syncthreads();
-  return incl - v;
+  const int w0 = buf[0], w1 = buf[1], w2 = buf[2], w3 = buf[3];
+  *tot = w0 + w1 + w2 + w3;
+  const int base = wave == 0 ? 0 : wave == 1 ? w0 : wave == 2 ? w0 + w1 : w0 + w1 + w2;
+  __syncthreads();
+  return base + incl - v;
+}
+
+// The T best (smallest key) of the eligible candidates 0..n-1, in key order, to out[0..m);
+// returns m = min(T, eligible), or -1 when the shortcut below does not apply (the caller then
+// sorts everything).  T <= 255.  Instead of sorting all candidates, a two-level histogram over the
+// key's leading bits (the probability's exponent, then its top 8 mantissa bits) finds a prefix
+// bound that at least T candidates meet; the few that meet it (T plus the occupants of one
+// histogram cell, at most 256 or the shortcut is off) are ranked against each other directly.
+// Keys are unique (they end in the creation index), so ranks are a permutation.
+template <typename Elig>
+__device__ int select_best(TreeLds& s, int n, int T, Elig eligible, int32_t* out) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  if (T <= 0) return 0;
+  // first histogram cell (scanning from the best) at which the running count reaches `want`
+  auto find_cell = [&](int want, int32_t* cell, int32_t* before) {
+    if (tid < 64) {
+      int c[4], sum = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { c[q] = s.scan[4 * lane + q]; sum += c[q]; }
+      int incl = sum;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        int x = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += x;
+      }
+      int run = incl - sum, found = -1, bef = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (found < 0 && run + c[q] >= want) { found = 4 * lane + q; bef = run; }
+        run += c[q];
+      }
+      const unsigned long long hit = __builtin_amdgcn_ballot_w64(found >= 0);
+      if (hit) {
+        const int src = __builtin_ctzll(hit);
+        found = __builtin_amdgcn_readlane(found, src);
+        bef = __builtin_amdgcn_readlane(bef, src);
+      } else {
+        found = 256;                                   // fewer than `want` in all cells: everything qualifies
+        bef = __builtin_amdgcn_readlane(incl, 63);
+      }
+      if (lane == 0) { *cell = found; *before = bef; }
+    }
+  };
+  if (tid == 0) { s.n_surv = 0; s.bin1 = 256; s.bin2 = 256; s.before1 = 0; }
+  if (n > 256) {
+    s.scan[tid] = 0;
+    __syncthreads();
+    for (int t = tid; t < n; t += 256)
+      if (eligible(t)) atomicAdd(&s.scan[(int)(cand_key(s.prob[t], t) >> 55) & 0xff], 1);
+    __syncthreads();
+    find_cell(T, &s.bin1, &s.before1);
+    __syncthreads();
+    const int b1 = s.bin1;
+    if (b1 < 256) {
+      s.scan[tid] = 0;
+      __syncthreads();
+      for (int t = tid; t < n; t += 256)
+        if (eligible(t)) {
+          const uint64_t kx = cand_key(s.prob[t], t);
+          if (((int)(kx >> 55) & 0xff) == b1) atomicAdd(&s.scan[(int)(kx >> 47) & 0xff], 1);
+        }
+      __syncthreads();
+      int32_t unused_before;
+      find_cell(T - s.before1, &s.bin2, tid == 0 ? &s.n_expand : &unused_before);   // n_expand: scratch
+    }
+  }
+  __syncthreads();
+  const int b1 = s.bin1, b2 = s.bin2;
+  for (int t = tid; t < n; t += 256)
+    if (eligible(t)) {
+      const uint64_t kx = cand_key(s.prob[t], t);
+      const int c1 = (int)(kx >> 55) & 0xff, c2 = (int)(kx >> 47) & 0xff;
+      if (c1 < b1 || (c1 == b1 && c2 <= b2)) {
+        const int idx = atomicAdd(&s.n_surv, 1);
+        if (idx < 256) s.key[idx] = kx;
+      }
+    }
+  __syncthreads();
+  const int ns = s.n_surv;
+  if (ns > 256) return -1;
+  if (tid < ns) {
+    const uint64_t kj = s.key[tid];
+    int rank = 0;
+    for (int i = 0; i < ns; ++i) rank += s.key[i] < kj ? 1 : 0;
+    if (rank < T) out[rank] = (int)(kj & 0xffffffffu);
+  }
+  __syncthreads();
+  return min(T, ns);
 }
 
 __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int32_t* __restrict__ topk_id,
@@ -247,9 +340,13 @@ __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int
     s.n_frontier = 1;
     s.bad = 0;
   }
+  for (int t = tid; t < p.k * kp; t += 256) {
+    s.list_id[t] = topk_id[(size_t)seq * p.k * kp + t];
+    s.list_p[t] = topk_p[(size_t)seq * p.k * kp + t];
+  }
   __syncthreads();
-  const int32_t* ids = topk_id + (size_t)seq * p.k * kp;
-  const float* ps = topk_p + (size_t)seq * p.k * kp;
+  const int32_t* ids = s.list_id;
+  const float* ps = s.list_p;
 
   for (int i = 1; i <= depth_limit; ++i) {
     // nodes of the current set at depth i-1, in (P desc, creation asc) order, first expand_width
@@ -310,6 +407,13 @@ __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int
       } else {
         // node set <- the B-i most probable candidates not used before
         const int n = s.n_total;
+        const int got = select_best(s, n, max(p.B - i, 0), [&](int t) { return !s.used[t]; }, s.frontier);
+        if (got >= 0) {
+          if (tid < got) s.used[s.frontier[tid]] = 1;
+          if (tid == 0) s.n_frontier = got;
+          __syncthreads();
+          continue;
+        }
         int n2 = 1;
         while (n2 < n) n2 <<= 1;
         for (int t = tid; t < n2; t += 256)
@@ -340,18 +444,21 @@ __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int
   // final selection: root + the B-1 most probable of all candidates (static: all of them)
   const int n = s.n_total;
   int n_keep = n - 1;
+  int32_t* kept = s.expand;                 // kept candidates in selection order (free after the loop)
   if (!s.bad) {
-    int n2 = 1;
-    while (n2 < n) n2 <<= 1;
     if (!is_static) {
-      for (int t = tid; t < n2; t += 256) s.key[t] = (t >= 1 && t < n) ? cand_key(s.prob[t], t) : ~0ull;
-      __syncthreads();
-      bitonic_sort(s.key, n2);
       n_keep = min(n - 1, max(p.B - 1, 0));
-    } else {
-      for (int t = tid; t < n2; t += 256) s.key[t] = (t >= 1 && t < n) ? (uint64_t)t : ~0ull;
-      __syncthreads();
-      bitonic_sort(s.key, n2);
+      const int got = select_best(s, n, n_keep, [](int t) { return t >= 1; }, kept);
+      if (got < 0) {
+        int n2 = 1;
+        while (n2 < n) n2 <<= 1;
+        for (int t = tid; t < n2; t += 256) s.key[t] = (t >= 1 && t < n) ? cand_key(s.prob[t], t) : ~0ull;
+        __syncthreads();
+        bitonic_sort(s.key, n2);
+        if (tid < n_keep) kept[tid] = (int)(s.key[tid] & 0xffffffffu);
+      }
+    } else if (n_keep + 1 <= ESP_MAX_TREE_NODES) {
+      if (tid < n_keep) kept[tid] = tid + 1;              // fixed tree: every candidate, creation order
     }
     if (n_keep + 1 > ESP_MAX_TREE_NODES) {
       if (tid == 0) s.bad = 1;
@@ -364,7 +471,7 @@ __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int
   }
   // rows: kept nodes ordered by (depth, creation); n_keep <= 255 so one thread per kept node
   int my = -1, my_rank = 0;
-  if (tid < n_keep) my = (int)(s.key[tid] & 0xffffffffu);
+  if (tid < n_keep) my = kept[tid];
   __syncthreads();
   if (tid < n_keep) s.scan[tid] = my;
   __syncthreads();
