@@ -245,6 +245,38 @@ def test_build_prune_tree_bit_exact(B, tiny_engine, Bn, k, K, kp, width, layout,
         check_block(nxt, b, tok, par, k, layout)
 
 
+def test_build_prune_tree_with_every_probability_tied(B, tiny_engine):
+    """All list entries carry the same probability (a power of two, so the products are exact and
+    equal per depth): every selection is decided by creation order alone, and the hundreds of
+    candidates that share one probability defeat the histogram shortcut of the selection, so the
+    full sort behind it runs.  Bit-exact against the oracle."""
+    shape, w, eng = tiny_engine
+    Bn, k, K, kp, layout = 96, 5, 10, 12, 0
+    batch = 2
+    rows = Bn * (k + 1)
+    nxt = B.BlockBuffers(batch, rows, k, layout)
+    rng = np.random.default_rng(77)
+    ids = np.stack([np.stack([rng.permutation(500)[:kp] for _ in range(k)]) for _ in range(batch)]).astype(np.int32)
+    ps = np.full((batch, k, kp), 0.0625, dtype=np.float32)
+    ps[1, :, 0] = 0.125                                   # sequence 1: one better entry per list, ties below it
+    n_lists = np.array([k, k], dtype=np.int32)
+    n_emit = np.array([1, 1], dtype=np.int32)
+    emit = np.zeros((batch, B.MAX_MASKS + 1), dtype=np.int32)
+    emit[:, 0] = [501, 502]
+    params = B.tree_params(Bn, k, K, 0, True, False, layout, None)
+    dev = lambda a: torch.as_tensor(a).cuda()
+    eng.build_prune_tree(params, dev(ids), dev(ps), kp, dev(n_lists), dev(n_emit), dev(emit), nxt)
+    assert eng.device_status() == 0
+    op = O.TreeParams(B=Bn, k=k, K=K, expand_width=0, prune_parent=True)
+    for b in range(batch):
+        tok, par, _ = O.build_prune_tree(op, ids[b], ps[b], int(emit[b, 0]), n_depths=k)
+        r0 = b * rows
+        n = int(nxt.n_nodes[b])
+        assert n == len(tok)
+        assert nxt.tok[r0:r0 + n].tolist() == tok.tolist()
+        assert nxt.parent[r0:r0 + n].tolist() == par.tolist()
+
+
 # ---------------------------------------------------------------------------------------- verify + KV commit
 def test_verify_accept_and_kv_commit(B, tiny_engine):
     shape, w, eng = tiny_engine
