@@ -230,8 +230,13 @@ def stage_rooflines(B, synth, torch, shape, lm_head_packed):
                                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": ms}
     del A, scratch
-    for rows in (4, 256, 1344):
-        lg = C_out[:rows]
+    for rows in (4, 64, 256, 1024, 1344, 4096):
+        if rows <= M:
+            lg = C_out[:rows]                      # logits of the GEMM above
+        else:
+            del C_out
+            C_out = torch.empty((rows, N), dtype=torch.float32, device="cuda").normal_(0.0, 2.0)
+            lg = C_out
         bufs = (torch.empty((rows, 10), dtype=torch.int32, device="cuda"),
                 torch.empty((rows, 10), dtype=torch.float32, device="cuda"),
                 torch.empty(max(B.load_library().esp_softmax_topk_scratch_bytes(rows, N, 10), 256), dtype=torch.uint8,
