@@ -203,6 +203,7 @@ esp_status esp_create(const esp_model_desc* m, const esp_weights* w, int32_t max
       !w->norm_attn || !w->norm_mlp)
     return ESP_EINVAL;
   if (m->qk_norm && (!w->q_norm || !w->k_norm)) return ESP_EINVAL;
+  if (gemm_prepare() != hipSuccess) return ESP_EDEVICE;
   if (((uintptr_t)workspace) % 256) return ESP_EINVAL;
   for (int l = 0; l < m->n_layers; ++l) {
     if (!w->wqkv[l] || !w->wo[l] || !w->w_gate_up[l] || !w->w_down[l] || !w->norm_attn[l] || !w->norm_mlp[l])

@@ -511,6 +511,17 @@ __global__ void k_pack_weight(const bf16_t* __restrict__ src, bf16_t* __restrict
   reinterpret_cast<uint4*>(dst)[piece] = *reinterpret_cast<const uint4*>(src + (size_t)n * K + k);
 }
 
+// The ring kernels use more dynamic LDS than a kernel gets by default: raise the limit once per
+// kernel (gemm_prepare does it for all of them when a context is created, so that no launch inside
+// a stream capture is the first one).
+template <int MT, int NB, int EPI>
+hipError_t ring_allow_lds() {
+  static const hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_bf16_ring<MT, NB, EPI>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)ring_lds_bytes<MT, NB>());
+  return attr;
+}
+
 template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), int EPI = 0>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
                        int N, int K, const GemmPlan& p, int a_ld = 0, float* out2 = nullptr,
@@ -520,9 +531,7 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
   size_t lds = 2 * (size_t)MT * 32 * A_ROW_BYTES;
   if constexpr (MT * NB >= 8 && TILED) {
     auto kern = k_gemm_bf16_ring<MT, NB, EPI>;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       (int)ring_lds_bytes<MT, NB>());
+    const hipError_t attr = ring_allow_lds<MT, NB, EPI>();
     if (attr != hipSuccess) return attr;
     const size_t ring_bytes = ring_lds_bytes<MT, NB>();
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), ring_bytes, st, (const bf16_t*)A, a_rows,
@@ -538,6 +547,14 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
 }
 
 }  // namespace
+
+hipError_t gemm_prepare() {
+  hipError_t e = ring_allow_lds<4, 2, 0>();
+  if (e == hipSuccess) e = ring_allow_lds<4, 2, 2>();
+  if (e == hipSuccess) e = ring_allow_lds<5, 2, 0>();
+  if (e == hipSuccess) e = ring_allow_lds<5, 2, 2>();
+  return e;
+}
 
 GemmPlan gemm_plan(int dtype, int M, int N, int K) {
   GemmPlan p;

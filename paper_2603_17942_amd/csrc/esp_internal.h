@@ -83,6 +83,8 @@ hipError_t launch_gemm(hipStream_t st, int dtype, const void* A, const int32_t* 
                        float* out, int M, int N, int K, const GemmPlan& p, bool w_packed, int a_ld = 0);
 // a_ld == 0: A is row-major [rows][K]; a_ld > 0 (bf16 only): A is chunk-major [K/64][a_ld][64]
 hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N, int K);
+// one-time kernel attributes of the GEMM kernels (dynamic LDS limits); call before the first launch
+hipError_t gemm_prepare();
 hipError_t launch_gemm_swiglu(hipStream_t st, const void* A, const void* W, void* act, int M, int ff, int K);
 // LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows, one split)
 bool gemm_argmax_supported(int dtype, int M, int N, int K);
