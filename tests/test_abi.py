@@ -80,6 +80,9 @@ def test_null_context_and_stage_calls_validate(lib):
     assert lib.esp_build_prune_tree(None, None, None, None, 4, None, None, None, C.byref(blk)) == 1
     assert lib.esp_block_from_tree(None, C.byref(blk)) == 1
     assert lib.esp_profile_enable(None, 1) == 1
+    assert lib.esp_mask_mean(None, 4096, 4, 2, 4096) == 1
+    assert lib.esp_mask_last_k(None, 4096, 4, 2, 4096) == 1
+    assert lib.esp_mask_gaussian(None, None, 0.0, 2, 4096) == 1
     # stage entry points: shapes and sizes are checked before anything is launched
     p = 4096
     assert lib.esp_gemm(None, B.ESP_BF16, p, p, 0, p, 4, 48, 64, p, 1 << 20) == 2      # N % 32
