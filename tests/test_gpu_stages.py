@@ -29,7 +29,8 @@ def rel_err_rows(got, want):
 
 # ---------------------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("M,N,K", [(1, 32, 64), (5, 96, 64), (68, 384, 512), (33, 128, 4096), (97, 2048, 1024),
-                                   (200, 640, 1024), (320, 512, 4096), (130, 6144, 512), (64, 1056, 256)])
+                                   (200, 640, 1024), (320, 512, 4096), (130, 6144, 512), (64, 1056, 256),
+                                   (200, 256, 64), (160, 96, 128), (129, 32, 192), (1344, 512, 256)])
 def test_gemm_bf16(B, M, N, K):
     print(f"gemm bf16 M={M} N={N} K={K}", flush=True)
     a = synth.normal_like((M, K), 1.0, 11, 0, "cuda", torch.bfloat16)
