@@ -55,11 +55,14 @@ def measured_traffic(layout, rows):
     return None
 
 
+PREFILL_CHUNK = int(os.environ.get("ESP_BENCH_PREFILL_CHUNK", "512"))   # rows per prefill block
+
+
 def run_config(B, decode, synth, torch, shape, weights, eng_holder, layout, n_nodes, k, K, kp, L, steps, warmup,
                prompt, profile_every=4):
     params = B.tree_params(n_nodes, k, K, 0, True, False, layout)
     cap = L + (steps + warmup + 16) * (k + 1) + 1024
-    dec = decode.EspDecoder(shape, weights, params, kp, [cap], prefill_chunk=256, engine=eng_holder.get("eng"))
+    dec = decode.EspDecoder(shape, weights, params, kp, [cap], prefill_chunk=PREFILL_CHUNK, engine=eng_holder.get("eng"))
     eng_holder["eng"] = dec.eng
     eng = dec.eng
     torch.cuda.synchronize()
@@ -369,7 +372,7 @@ def main():
         "roofline": sm["roofline"], "roofline_attn": sm["roofline_attn"],
         "breakdown_ms_per_step": sm["breakdown_ms_per_step"],
         "setup_s": round(t_setup, 1),
-        "prefill": {"prompt_tokens": L, "chunk_rows": 256, "ms": round(main_r["prefill_ms"], 2),
+        "prefill": {"prompt_tokens": L, "chunk_rows": PREFILL_CHUNK, "ms": round(main_r["prefill_ms"], 2),
                     "tokens_per_s": round((L - 1) / (main_r["prefill_ms"] * 1e-3), 0),
                     "note": "untimed setup of the step workload, host-synchronised once at the end"},
     }
