@@ -215,8 +215,12 @@ class BlockBuffers:
 class Engine:
     """One esp_ctx plus the device tensors it works on.  Method names follow the C entry points."""
 
+    GUARD_BYTE = 0xA5
+
     def __init__(self, shape: synth.ModelShape, weights: dict, max_batch: int, max_rows_per_seq: int,
-                 max_kv_len: int, device="cuda"):
+                 max_kv_len: int, device="cuda", guard_bytes: int = 0):
+        """guard_bytes > 0 places the workspace between two guard regions of that many bytes filled
+        with GUARD_BYTE (guards_intact() checks them): a test hook, no effect on the library."""
         if not torch.cuda.is_available():
             raise RuntimeError("the ESP HIP path needs a GPU; there is no CPU fallback")
         self.lib = load_library()
@@ -264,8 +268,10 @@ class Engine:
         nbytes = self.lib.esp_workspace_bytes(C.byref(self.desc), max_batch, max_rows_per_seq, max_kv_len)
         if nbytes == 0:
             raise EspError(1, "esp_workspace_bytes")
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
-        ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
+        guard = (int(guard_bytes) + 255) // 256 * 256
+        self.workspace = torch.full((nbytes + 256 + 2 * guard,), self.GUARD_BYTE, dtype=torch.uint8, device=device)
+        ws_ptr = (self.workspace.data_ptr() + guard + 255) // 256 * 256
+        self._ws_off, self._ws_bytes = ws_ptr - self.workspace.data_ptr(), nbytes
         ctx = _vp()
         _check(self.lib.esp_create(C.byref(self.desc), C.byref(wst), max_batch, max_rows_per_seq, max_kv_len,
                                    ws_ptr, nbytes, _stream_ptr(), C.byref(ctx)), "esp_create")
@@ -281,6 +287,12 @@ class Engine:
         ff, d = gate.shape
         assert ff % 32 == 0
         return torch.stack([gate.reshape(ff // 32, 32, d), up.reshape(ff // 32, 32, d)], 1).reshape(2 * ff, d)
+
+    def guards_intact(self) -> bool:
+        """True when every byte of the allocation outside the workspace still holds GUARD_BYTE."""
+        lo = self.workspace[:self._ws_off]
+        hi = self.workspace[self._ws_off + self._ws_bytes:]
+        return bool((lo == self.GUARD_BYTE).all().item()) and bool((hi == self.GUARD_BYTE).all().item())
 
     def close(self):
         if getattr(self, "ctx", None):
@@ -437,3 +449,4 @@ def softmax_topk(logits: torch.Tensor, kp: int, bufs=None):
     _check(lib.esp_softmax_topk(_stream_ptr(), _ptr(logits), rows, vocab, kp, _ptr(ids), _ptr(ps), _ptr(scratch),
                                 nb), "esp_softmax_topk")
     return ids, ps
+

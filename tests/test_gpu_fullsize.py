@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from util import O, oracle_model, small_shape, synth, to_np
+from util import O, identical_logits_leg, oracle_model, small_shape, synth, to_np
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -57,9 +57,31 @@ def test_step_at_full_width_two_layer_cut(B, name, layout, n_nodes, k, K, kp, L)
     dec.mask_embed.copy_(masks)
     R = dec.rows_per_seq
     dec.logits_dbg = torch.zeros((R, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.mask_logits = torch.zeros((1, k, shape.vocab), dtype=torch.float32, device="cuda")
     dec.step()
     assert dec.eng.device_status() == 0
     torch.cuda.synchronize()
+    # identical-logits leg (unconditional): arg-max, accepted path, cache length, Top-K' ids and the
+    # next tree, exactly, from the logits the GPU itself produced
+    op = O.TreeParams(B=n_nodes, k=k, K=K, expand_width=0)
+    info = identical_logits_leg(dec, 0, tok.numpy(), par.numpy(), k, layout, kp, op, L,
+                                dec.logits_dbg.cpu().numpy(), dec.mask_logits[0].cpu().numpy())
+    print(f"identical-logits leg: {info}", flush=True)
+    # the same step without debug outputs (the configuration bench.py times) decides the same integers
+    fused = decode.EspDecoder(shape, w, params, kp, [L + 1024], prefill_chunk=64, engine=dec.eng)
+    for l in range(shape.n_layers):
+        fused.eng.kv_store(fused.kv, l, 0, 0, kf[l].contiguous(), vf[l].contiguous())
+    fused.kv.set_len([L])
+    fused.set_tree([tok.tolist()], [par.tolist()])
+    fused.mask_embed.copy_(masks)
+    fused.step()
+    assert fused.eng.device_status() == 0
+    assert torch.equal(fused.node_argmax[:n_nodes], dec.node_argmax[:n_nodes])
+    assert fused.emitted() == dec.emitted()
+    assert torch.equal(fused.topk_id, dec.topk_id) and torch.equal(fused.topk_p, dec.topk_p)
+    assert torch.equal(fused.cur.tok, dec.cur.tok) and torch.equal(fused.cur.parent, dec.cur.parent)
+    assert torch.equal(fused.cur.anc, dec.cur.anc)
+    del fused
     print("gpu step done; oracle ...", flush=True)
 
     m = oracle_model(shape, w)
@@ -83,6 +105,8 @@ def test_step_at_full_width_two_layer_cut(B, name, layout, n_nodes, k, K, kp, L)
             all_decisive = False
     hid_gpu = to_np(dec.hidden[:R])
     assert rel_err_rows(hid_gpu, hidden) <= TOL
+    print(f"tree rows whose oracle arg-max margin is inside the band: "
+          f"{sum(not decisive(node_logits[r]) for r in range(n_nodes))} of {n_nodes}", flush=True)
     if all_decisive:
         n_star, accepted, emitted = O.verify_accept(blk.tok, blk.parent, g)
         ne = int(dec.n_emit[0])
@@ -229,10 +253,16 @@ def test_batched_step_against_oracle(B, Bn, nodes):
     dec.mask_embed.copy_(masks)
     R = dec.rows_per_seq
     dec.logits_dbg = torch.zeros((3 * R, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.mask_logits = torch.zeros((3, k, shape.vocab), dtype=torch.float32, device="cuda")
     dec.step()
     assert dec.eng.device_status() == 0
     lg = dec.logits_dbg.cpu().numpy()
     emitted = dec.emitted()
+    op = O.TreeParams(B=Bn, k=k, K=K, expand_width=0)
+    for b in range(3):     # identical-logits leg, unconditional, per sequence
+        info = identical_logits_leg(dec, b, trees[b][0].numpy(), trees[b][1].numpy(), k, layout, kp, op, lens[b],
+                                    lg[b * R:(b + 1) * R], dec.mask_logits[b].cpu().numpy())
+        print(f"  seq {b}: {info}", flush=True)
     for b in range(3):
         kf, vf = fills[b]
         st = O.DecodeState([to_np(kf[l]) for l in range(shape.n_layers)], [to_np(vf[l]) for l in range(shape.n_layers)],
@@ -315,3 +345,99 @@ def test_qwen3_shape_256_token_generation_loop(B):
     assert accepted >= 60                # about a third of the steps carry three true tokens
     decode.EspDecoder.default_max_rows = 0
     eng.close()
+
+
+def test_config5_batched_step_at_full_size(B):
+    """configs[4] as a whole step: 16 independent sequences, KV lengths uniform in [512, 8192] and
+    trees of 32..128 nodes (both seeded), k = 4 mask tokens per node (block complexity 5 N, up to 640
+    rows per sequence, 10240-row block), Top-K 8, Llama-3-8B widths, depth cut to two layers.
+    Every sequence: the integer chain of the step, exactly, on the GPU's own logits.  Two sampled
+    sequences (the cheapest and the costliest for the oracle): logits, hidden states and committed
+    K/V against the oracle's forward."""
+    from paper_2603_17942_amd import decode
+    shape = synth.SHAPES["llama3_8b"].replace(n_layers=2)
+    batch, k, K, kp, layout, Bn = 16, 4, 8, 10, 0, 128
+    lens = (512 + synth.uniform_ints(batch, 8192 - 512 + 1, 3, 0)).tolist()
+    nodes = (32 + synth.uniform_ints(batch, 128 - 32 + 1, 4, 0)).tolist()
+    print(f"config 5 step: lens={lens} nodes={nodes}", flush=True)
+    w = synth.make_weights(shape, seed=1, device="cuda")
+    params = B.tree_params(Bn, k, K, 0, True, False, layout)
+    dec = decode.EspDecoder(shape, w, params, kp, [l + 640 + 64 for l in lens], prefill_chunk=64)
+    R = dec.rows_per_seq
+    assert R == 640
+    cost = [lens[b] * nodes[b] for b in range(batch)]
+    sampled = sorted({int(np.argmin(cost)), int(np.argmax(cost))})
+    fills = {}
+    for b in range(batch):
+        kf, vf = synth.make_kv_fill(shape, lens[b], seed=40 + b, device="cuda")
+        for l in range(shape.n_layers):
+            dec.eng.kv_store(dec.kv, l, b, 0, kf[l].contiguous(), vf[l].contiguous())
+        if b in sampled:
+            fills[b] = (kf, vf)
+    dec.kv.set_len(lens)
+    trees = [synth.make_random_tree(nodes[b], k, shape.vocab, seed=60 + b) for b in range(batch)]
+    dec.set_tree([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])
+    masks = synth.normal_like((k, shape.d_model), 0.02, 6, 0, "cuda", torch.bfloat16)
+    dec.mask_embed.copy_(masks)
+    dec.logits_dbg = torch.zeros((batch * R, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.mask_logits = torch.zeros((batch, k, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.step()
+    assert dec.eng.device_status() == 0
+    torch.cuda.synchronize()
+    print("gpu step done", flush=True)
+    op = O.TreeParams(B=Bn, k=k, K=K, expand_width=0)
+    total_acc = 0
+    for b in range(batch):
+        info = identical_logits_leg(dec, b, trees[b][0].numpy(), trees[b][1].numpy(), k, layout, kp, op, lens[b],
+                                    dec.logits_dbg[b * R:(b + 1) * R].cpu().numpy(), dec.mask_logits[b].cpu().numpy())
+        total_acc += info["accepted"]
+    print(f"identical-logits leg green for all {batch} sequences", flush=True)
+    # the configuration bench.py times (no debug outputs): same integers from the same state
+    fused = decode.EspDecoder(shape, w, params, kp, [l + 640 + 64 for l in lens], prefill_chunk=64, engine=dec.eng)
+    for b in range(batch):
+        kf, vf = fills[b] if b in fills else synth.make_kv_fill(shape, lens[b], seed=40 + b, device="cuda")
+        for l in range(shape.n_layers):
+            fused.eng.kv_store(fused.kv, l, b, 0, kf[l].contiguous(), vf[l].contiguous())
+    fused.kv.set_len(lens)
+    fused.set_tree([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])
+    fused.mask_embed.copy_(masks)
+    fused.step()
+    assert fused.eng.device_status() == 0
+    assert fused.emitted() == dec.emitted()
+    assert torch.equal(fused.star_row, dec.star_row) and torch.equal(fused.kv.len, dec.kv.len)
+    assert torch.equal(fused.topk_id, dec.topk_id) and torch.equal(fused.topk_p, dec.topk_p)
+    assert torch.equal(fused.cur.tok, dec.cur.tok) and torch.equal(fused.cur.parent, dec.cur.parent)
+    for b in range(batch):
+        assert torch.equal(fused.node_argmax[b * R:b * R + nodes[b]], dec.node_argmax[b * R:b * R + nodes[b]])
+    del fused
+    # oracle forward of the sampled sequences
+    m = oracle_model(shape, w)
+    for b in sampled:
+        print(f"oracle forward of sequence {b}: L={lens[b]} nodes={nodes[b]}", flush=True)
+        kf, vf = fills[b]
+        kc = [to_np(kf[l]) for l in range(shape.n_layers)]
+        vc = [to_np(vf[l]) for l in range(shape.n_layers)]
+        blk = O.make_block(trees[b][0].numpy(), trees[b][1].numpy(), k, layout)
+        rb = blk.n_rows
+        _, hidden, k_new, v_new = O.tree_forward(m, blk, to_np(masks), kc, vc, lens[b], want_logits_rows=[])
+        assert rel_err_rows(to_np(dec.hidden[b * R:b * R + rb]), hidden) <= TOL
+        node_logits = O.lm_head_logits(m, hidden[:nodes[b]])
+        assert rel_err_rows(dec.logits_dbg[b * R:b * R + nodes[b]].cpu().numpy(), node_logits) <= TOL
+        g = np.argmax(node_logits, axis=1)
+        g_gpu = dec.node_argmax[b * R:b * R + nodes[b]].cpu().numpy()
+        banded = 0
+        for r in range(nodes[b]):
+            if decisive(node_logits[r]):
+                assert g_gpu[r] == g[r], (b, r)
+            else:
+                banded += 1
+        print(f"  tree rows inside the band: {banded} of {nodes[b]}", flush=True)
+        ne = int(dec.n_emit[b])
+        keep = dec.accepted_row[b, :ne].tolist()
+        for l in range(shape.n_layers):
+            kk, vv = dec.eng.kv_load(dec.kv, l, b, lens[b], ne)
+            assert rel_err_rows(to_np(kk).reshape(ne, -1), k_new[l][keep].reshape(ne, -1)) <= TOL
+            assert rel_err_rows(to_np(vv).reshape(ne, -1), v_new[l][keep].reshape(ne, -1)) <= TOL
+        # rows past the sequence's block stay zero
+        assert float(dec.hidden[b * R + rb:(b + 1) * R].float().abs().max()) == 0.0 if rb < R else True
+    dec.eng.close()

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from util import O, oracle_model, small_shape, synth, to_np
+from util import O, identical_logits_leg, oracle_model, small_shape, synth, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -229,13 +229,37 @@ def test_bf16_step_against_oracle(B, qk_norm, layout, n_nodes, k, L):
     dec.mask_embed.copy_(masks)
     M = dec.rows_per_seq
     dec.logits_dbg = torch.zeros((M, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.mask_logits = torch.zeros((1, k, shape.vocab), dtype=torch.float32, device="cuda")
     st = O.DecodeState([to_np(kf[l]) for l in range(shape.n_layers)], [to_np(vf[l]) for l in range(shape.n_layers)],
                        L, tok.numpy().astype(np.int64), par.numpy().astype(np.int64), to_np(masks))
     op = O.TreeParams(B=n_nodes, k=k, K=K, expand_width=0)
     res = O.esp_step(m, st, op, layout, kp, "bf16")
     dec.step()
     assert dec.eng.device_status() == 0
-    compare_step(dec, res, n_nodes, M, shape, kp, TOL["bf16"], dec.logits_dbg.cpu().numpy(), None)
+    lg_gpu = dec.logits_dbg.cpu().numpy()
+    # oracle leg: logits within the band; integers where the oracle's margin is decisive
+    full = compare_step(dec, res, n_nodes, M, shape, kp, TOL["bf16"], lg_gpu, None)
+    banded = sum(not decisive(res.logits[r], TOL["bf16"]) for r in range(n_nodes))
+    # identical-logits leg: every integer of the step, exactly, on the logits the GPU produced
+    info = identical_logits_leg(dec, 0, tok.numpy(), par.numpy(), k, layout, kp, op, L, lg_gpu[:res.logits.shape[0]],
+                                dec.mask_logits[0].cpu().numpy())
+    print(f"  oracle-logits chain compared to the end: {full}; tree rows inside the band: {banded} of {n_nodes}; "
+          f"identical-logits leg: {info}", flush=True)
+    # the path without debug outputs (arg-max in the LM-head epilogue, logits kept or never written)
+    # takes the same integer decisions from the same state
+    fused = decode.EspDecoder(shape, w, params, kp, [L + 1024], prefill_chunk=64, engine=dec.eng)
+    for l in range(shape.n_layers):
+        fused.eng.kv_store(fused.kv, l, 0, 0, kf[l].contiguous(), vf[l].contiguous())
+    fused.kv.set_len([L])
+    fused.set_tree([tok.tolist()], [par.tolist()])
+    fused.mask_embed.copy_(masks)
+    fused.step()
+    assert fused.eng.device_status() == 0
+    assert torch.equal(fused.node_argmax[:n_nodes], dec.node_argmax[:n_nodes])
+    assert fused.emitted() == dec.emitted()
+    assert torch.equal(fused.topk_id, dec.topk_id) and torch.equal(fused.topk_p, dec.topk_p)
+    assert torch.equal(fused.cur.tok, dec.cur.tok) and torch.equal(fused.cur.parent, dec.cur.parent)
+    assert torch.equal(fused.cur.anc, dec.cur.anc) and int(fused.kv.len[0]) == int(dec.kv.len[0])
     # hidden states of the block rows against the oracle's K/V written into the cache
     R = res.logits.shape[0]
     blk = O.make_block(tok.numpy(), par.numpy(), k, layout)

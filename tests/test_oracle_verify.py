@@ -205,3 +205,53 @@ def test_sampled_esp_loop_reproduces_plain_sampled_decoding(layout, width):
             st.tok, st.parent = np.asarray(tok), np.asarray(parent)
     assert out[:n_new] == ref[:n_new]
     assert accepted_total >= 4
+
+
+def test_round_like_bf16_is_round_to_nearest_even():
+    """Storage rounding of the KV cache and mask vectors (bf16 workloads) pinned to the IEEE rule
+    through torch's own float32 -> bfloat16 conversion and through hand-built cases: bf16 keeps the
+    top 16 bits of a float32, a value exactly half way between two neighbours goes to the one whose
+    last kept bit is 0, everything else to the nearer one.  Truncation, round-half-up and
+    round-half-away all fail one of the hand-built cases."""
+    import torch
+
+    def f32_from_bits(bits):
+        return np.asarray(bits, dtype=np.uint32).view(np.float32)
+
+    base = 0x3F800000                    # 1.0; bf16 neighbours are 0x10000 apart in float32 bits
+    cases_bits = [
+        base + 0x8000,                   # half way, kept bit 0 -> down to 1.0
+        base + 0x18000,                  # half way, kept bit 1 -> up (round to even)
+        base + 0x7FFF,                   # just below half -> down
+        base + 0x8001,                   # just above half -> up
+        base + 0x28000,                  # half way, kept bit 0 -> down
+        0xBF800000 + 0x8000,             # negative half way, kept bit 0 -> towards zero (-1.0)
+        0xBF800000 + 0x18000,            # negative half way, kept bit 1 -> away from zero
+        0x3F7F8000,                      # half way below 1.0 with kept bit 1 -> carries into the exponent: 1.0
+        0x00008000, 0x00018000,          # subnormal float32 inputs
+        0x7F7F7FFF,                      # largest value that stays finite
+        0x00000000, 0x80000000,
+    ]
+    want_bits = [base, base + 0x20000, base, base + 0x10000, base + 0x20000,
+                 0xBF800000, 0xBF800000 + 0x20000, 0x3F800000, 0x00000000, 0x00020000, 0x7F7F0000,
+                 0x00000000, 0x80000000]
+    x = f32_from_bits(cases_bits)
+    got = O.round_like(x, "bf16")
+    assert got.dtype == np.float64
+    assert np.array_equal(got.astype(np.float32).view(np.uint32), np.asarray(want_bits, dtype=np.uint32))
+    # library conversion on the same cases and on a seeded sweep (weights-like and cache-like scales)
+    lib = torch.from_numpy(x.copy()).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got.astype(np.float32).view(np.uint32), lib.view(np.uint32))
+    for std, seed in [(0.02, 3), (1.0, 4), (300.0, 5)]:
+        v = synth.normal_like((50000,), std, seed, 0, "cpu", torch.float32)
+        lib = v.to(torch.bfloat16).to(torch.float64).numpy()
+        assert np.array_equal(O.round_like(v.numpy(), "bf16"), lib)
+    # float64 inputs are first rounded to float32 (the GPU holds these values in fp32 before the store)
+    y = np.asarray([1.0 + 2.0 ** -8 + 2.0 ** -40, 1.0 + 2.0 ** -8 - 2.0 ** -40])
+    assert O.round_like(y, "bf16").tolist() == [1.0, 1.0]          # both collapse to the fp32 tie 1 + 2^-8 -> even
+    # the other storage types
+    z = np.asarray([1.0 + 2.0 ** -30, np.pi])
+    assert np.array_equal(O.round_like(z, "f32"), z.astype(np.float32).astype(np.float64))
+    assert np.array_equal(O.round_like(z, "f64"), z)
+    with pytest.raises(ValueError):
+        O.round_like(z, "fp8")
