@@ -329,6 +329,13 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
   const AttnPlan ap = attn_plan(blk->batch, blk->rows_per_seq, hq, hkv, kv->len_bound);
   if (attn_partial_floats(blk->batch, blk->rows_per_seq, hq, hd, ap.nsplit) > c->attn_part_floats)
     return ESP_ECAPACITY;
+  // the LM-head passes below need an unsplit plan (their epilogues see whole rows): refuse before
+  // anything is launched, so that no K/V has been appended when the call fails
+  if (logits_dbg || node_argmax) {
+    const int Mlm = logits_dbg ? M : blk->batch * nodes_bound(blk);
+    if (!logits_dbg && (size_t)Mlm > c->logits_rows) return ESP_ECAPACITY;
+    if (gemm_plan(dt, Mlm, m.vocab, d).splits != 1) return ESP_ESHAPE;
+  }
 
   { ESP_PROF(ESP_SITE_GLUE);
   ESP_HIP(launch_embed(s, dt, bd, kd, c->embed, mask_embed, c->h, d, m.vocab, c->rope_tab, hd, m.rope_theta,

@@ -43,7 +43,7 @@ constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_
 // text so that the compiler's wait-count bookkeeping knows nothing of it: the ring below counts
 // its own loads (they retire in order) and would otherwise be drained before every LDS read.
 __device__ __forceinline__ void load_to_lds16(const void* g, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
 }
 template <int N_YOUNGER>
 __device__ __forceinline__ void wait_loads_but() {
