@@ -312,6 +312,20 @@ esp_status esp_softmax_topk(void *stream, const float *logits, int32_t rows, int
                             int32_t Kp, int32_t *ids, float *probs, void *scratch,
                             size_t scratch_bytes);
 
+/* esp_softmax_topk for callers that cannot allocate or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the per-segment records live in a
+ * device array that is part of the library image (2.06 MiB per GPU, held until the process ends)
+ * instead of `scratch`.  Same kernels, same results as esp_softmax_topk.  The call allocates
+ * nothing and synchronises nothing; the device that is current at the call must be the stream's.
+ * Limit: rows * min(64, ceil(vocab / 2048)) * (2 + 2 Kp) <= 128 * 64 * 66 floats, i.e. up to 128
+ * rows at any vocabulary and Kp (more rows for smaller vocabularies or Kp); beyond that
+ * ESP_ECAPACITY and nothing is launched.  All calls on one GPU share the one array: calls that
+ * overlap in time on the same GPU (different streams or threads) race; successive calls on one
+ * stream do not (every record a call reads it has written itself).
+ * Errors: EINVAL as esp_softmax_topk, ECAPACITY, EDEVICE (symbol lookup or launch failed). */
+esp_status esp_softmax_topk_static(void *stream, const float *logits, int32_t rows, int32_t vocab,
+                                   int32_t Kp, int32_t *ids, float *probs);
+
 /* Optional timing of launch sites with HIP events recorded on the ctx stream (benchmarks).
  * esp_profile_enable: bit s of site_mask turns site s on (0 = off, the default; events are host
  * objects, no device memory is allocated).  esp_profile_read: synchronises the stream, adds the

@@ -60,7 +60,7 @@ EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
            "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_mask_last_k", "esp_mask_gaussian", "esp_kv_store", "esp_kv_load",
            "esp_gemm_scratch_bytes", "esp_gemm", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
-           "esp_softmax_topk", "esp_profile_enable", "esp_profile_read", "esp_pack_weight", "esp_set_sampling"]
+           "esp_softmax_topk", "esp_softmax_topk_static", "esp_profile_enable", "esp_profile_read", "esp_pack_weight", "esp_set_sampling"]
 SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
 
 _lib = None
@@ -108,6 +108,7 @@ def load_library() -> C.CDLL:
     lib.esp_softmax_topk_scratch_bytes.restype = C.c_size_t
     lib.esp_softmax_topk_scratch_bytes.argtypes = [_i32, _i32, _i32]
     lib.esp_softmax_topk.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, C.c_size_t]
+    lib.esp_softmax_topk_static.argtypes = [_vp, _vp, _i32, _i32, _i32, _vp, _vp]
     lib.esp_profile_enable.argtypes = [_vp, C.c_uint32]
     lib.esp_set_sampling.argtypes = [_vp, C.c_int32, C.c_uint32]
     lib.esp_profile_read.argtypes = [_vp, _i32, P(_i64), P(C.c_double)]
@@ -450,3 +451,13 @@ def softmax_topk(logits: torch.Tensor, kp: int, bufs=None):
                                 nb), "esp_softmax_topk")
     return ids, ps
 
+
+def softmax_topk_static(logits: torch.Tensor, kp: int, ids: torch.Tensor, ps: torch.Tensor):
+    """esp_softmax_topk_static: as softmax_topk, but with the library's own device array as scratch
+    (no workspace argument, no allocation).  ids / ps are written in place."""
+    lib = load_library()
+    rows, vocab = logits.shape
+    assert ids.shape == (rows, kp) and ids.dtype == torch.int32 and ps.shape == (rows, kp) and ps.dtype == torch.float32
+    _check(lib.esp_softmax_topk_static(_stream_ptr(), _ptr(logits), rows, vocab, kp, _ptr(ids), _ptr(ps)),
+           "esp_softmax_topk_static")
+    return ids, ps

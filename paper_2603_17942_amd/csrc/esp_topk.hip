@@ -15,6 +15,7 @@
 // the segments' sorted lists (at most 64 segments, one per lane: K' rounds of a wave-wide best-head
 // search); p = exp(v - max) / sum in fp32.
 #include <algorithm>
+#include <mutex>
 
 #include "esp_internal.h"
 
@@ -89,9 +90,9 @@ __device__ __forceinline__ void offer(LaneList& L, float v, int my_id, float& bo
   }
 }
 
-// scratch per (row, segment): [max, sum, v_0..v_{kp-1}, id_0..id_{kp-1}] as 2 + 2*kp words
+// record per (row, segment): [max, sum, v_0..v_{kp-1}, id_0..id_{kp-1}] as 2 + 2*kp words
 __global__ __launch_bounds__(256) void k_topk_stream(const float* __restrict__ logits, int rows, int vocab, int kp,
-                                                     int nseg, int seg_len, float* __restrict__ scratch,
+                                                     int nseg, int seg_len, float* __restrict__ seg_rec,
                                                      const int32_t* __restrict__ row_map) {
   const int lane = threadIdx.x & 63;
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256) void k_topk_stream(const float* __restrict__ l
   const float wm = wave_max(m);
   const float contrib = m > -INFINITY ? s * __builtin_amdgcn_exp2f((m - wm) * LOG2E_F) : 0.f;
   const float ws = wave_sum(contrib);
-  float* out = scratch + ((size_t)row * nseg + seg) * (2 + 2 * kp);
+  float* out = seg_rec + ((size_t)row * nseg + seg) * (2 + 2 * kp);
   if (lane == 0) { out[0] = wm; out[1] = ws; }
   if (lane < kp) {
     out[2 + lane] = L.v;
@@ -166,13 +167,13 @@ __global__ __launch_bounds__(256) void k_topk_stream(const float* __restrict__ l
 
 // one wave per row: the segments' lists are sorted, so lane c walks segment c's list and the wave
 // takes the best head (value desc, id asc) K' times -- a 64-way merge of sorted lists
-__global__ __launch_bounds__(256) void k_topk_merge(const float* __restrict__ scratch, int rows, int kp, int nseg,
+__global__ __launch_bounds__(256) void k_topk_merge(const float* __restrict__ seg_rec, int rows, int kp, int nseg,
                                                     int32_t* __restrict__ ids, float* __restrict__ probs) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const int stride = 2 + 2 * kp;
-  const float* e = scratch + ((size_t)row * nseg + lane) * stride;     // this lane's segment (nseg <= 64)
+  const float* e = seg_rec + ((size_t)row * nseg + lane) * stride;     // this lane's segment (nseg <= 64)
   const bool have = lane < nseg;
   const float smax = have ? e[0] : -INFINITY;
   const float gmax = wave_max(smax);
@@ -218,7 +219,52 @@ int topk_segments(int rows, int vocab, int* seg_len) {
   return nseg;
 }
 
+// ---- entry point for callers that cannot allocate ---------------------------------------------
+// Per-(row, segment) statistics and candidate lists of the two-pass Top-K' in a file-scope device
+// array instead of a caller workspace.  Every GPU the library runs on holds its own copy of the
+// array (at its own address) until the process ends; the host-side name is only a handle for
+// hipGetSymbolAddress, whose result (per device) is what the kernels receive.
+constexpr int STATIC_MAX_ROWS = 128;
+constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)STATIC_MAX_ROWS * 64 * (2 + 2 * ESP_MAX_TOPK);   // 2.06 MiB
+static __device__ __align__(256) __attribute__((used)) float scratch[STATIC_SCRATCH_FLOATS];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static float* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each device, 0 = not looked up yet
+
+// device address of the array on the current device (looked up once per device)
+static hipError_t static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 }  // namespace
+
+extern "C" esp_status esp_softmax_topk_static(void* stream, const float* logits, int32_t rows, int32_t vocab,
+                                              int32_t Kp, int32_t* ids, float* probs) {
+  if (!logits || !ids || !probs) return ESP_EINVAL;
+  if (rows < 1 || vocab < 1 || Kp < 1 || Kp > ESP_MAX_TOPK || Kp > vocab) return ESP_EINVAL;
+  if (softmax_topk_scratch_floats(rows, vocab, Kp) > STATIC_SCRATCH_FLOATS) return ESP_ECAPACITY;
+  float* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return ESP_EDEVICE;
+  // every (row, segment) record the merge pass reads is written by the stream pass of the same
+  // call, so nothing of an earlier call's contents has to be cleared
+  if (launch_softmax_topk((hipStream_t)stream, logits, rows, vocab, Kp, ids, probs, ws, nullptr) != hipSuccess)
+    return ESP_EDEVICE;
+  return ESP_OK;
+}
 
 size_t softmax_topk_scratch_floats(int rows, int vocab, int kp) {
   int max_seg = std::min(64, (vocab + BLOCK - 1) / BLOCK);   // upper bound of the segment count for any row count
@@ -226,15 +272,15 @@ size_t softmax_topk_scratch_floats(int rows, int vocab, int kp) {
 }
 
 hipError_t launch_softmax_topk(hipStream_t st, const float* logits, int rows, int vocab, int kp, int32_t* ids,
-                               float* probs, float* scratch, const int32_t* row_map) {
+                               float* probs, float* ws, const int32_t* row_map) {
   if (rows <= 0) return hipSuccess;
   int seg_len = 0;
   const int nseg = topk_segments(rows, vocab, &seg_len);
   const int items = rows * nseg;
   hipLaunchKernelGGL(k_topk_stream, dim3((items + 3) / 4), dim3(256), 0, st, logits, rows, vocab, kp, nseg, seg_len,
-                     scratch, row_map);
+                     ws, row_map);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_topk_merge, dim3((rows + 3) / 4), dim3(256), 0, st, scratch, rows, kp, nseg, ids, probs);
+  hipLaunchKernelGGL(k_topk_merge, dim3((rows + 3) / 4), dim3(256), 0, st, ws, rows, kp, nseg, ids, probs);
   return hipGetLastError();
 }

@@ -108,3 +108,18 @@ def test_engine_refuses_to_run_without_a_gpu():
     shape = synth.SHAPES["tiny"]
     with pytest.raises(RuntimeError):
         B.Engine(shape, {"layers": []}, 1, 64, 512)
+
+
+def test_static_topk_rejects_on_the_host(lib):
+    """esp_softmax_topk_static validates before any HIP call: null pointers, bad Kp, and sizes
+    beyond its fixed device array (128 rows at the largest vocabulary and Kp)."""
+    one = C.c_void_p(256)      # never dereferenced: every case below is rejected first
+    f = lib.esp_softmax_topk_static
+    assert f(None, None, 4, 4096, 4, one, one) == 1
+    assert f(None, one, 4, 4096, 4, None, one) == 1
+    assert f(None, one, 0, 4096, 4, one, one) == 1
+    assert f(None, one, 4, 4096, 0, one, one) == 1
+    assert f(None, one, 4, 4096, B.MAX_TOPK + 1, one, one) == 1
+    assert f(None, one, 4, 3, 4, one, one) == 1                       # Kp > vocab
+    assert f(None, one, 132, 128256, 32, one, one) == 3               # ESP_ECAPACITY
+    assert f(None, one, 100000, 128256, 1, one, one) == 3
