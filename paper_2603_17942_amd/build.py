@@ -16,10 +16,16 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.j
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
+# per-source additions: the attention kernels never produce or test NaN / infinity (masked scores are a
+# large finite negative), and telling the compiler so drops the canonicalising copy in front of
+# every maximum of the online softmax
+EXTRA_FLAGS = {"esp_attn.hip": ["-fno-honor-nans"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(PKG, "_build", src.replace(".hip", ".o"))
     os.makedirs(os.path.dirname(obj), exist_ok=True)
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

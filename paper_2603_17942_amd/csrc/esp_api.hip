@@ -61,7 +61,7 @@ WsLayout ws_layout(const esp_model_desc* m, int max_batch, int max_rows, int64_t
   int lb = (int)std::min<int64_t>(max_kv_len, 0x7fffffff);
   AttnPlan ap = attn_plan(max_batch, max_rows, hq, hkv, lb);
   // a call may use fewer rows / shorter bound and hence another split count: size for the worst
-  size_t apf = attn_partial_floats(max_batch, max_rows, hq, hd, std::max(ap.nsplit, 64));
+  size_t apf = attn_partial_floats(m->dtype, max_batch, max_rows, hq, hkv, hd, std::max(ap.nsplit, 64));
   w.attn_part_floats = apf;
   w.attn_part = take(apf * 4);
   w.rope_tab = take(M * (size_t)hd * 4);
@@ -203,7 +203,7 @@ esp_status esp_create(const esp_model_desc* m, const esp_weights* w, int32_t max
       !w->norm_attn || !w->norm_mlp)
     return ESP_EINVAL;
   if (m->qk_norm && (!w->q_norm || !w->k_norm)) return ESP_EINVAL;
-  if (gemm_prepare() != hipSuccess) return ESP_EDEVICE;
+  if (gemm_prepare() != hipSuccess || attn_prepare() != hipSuccess) return ESP_EDEVICE;
   if (((uintptr_t)workspace) % 256) return ESP_EINVAL;
   for (int l = 0; l < m->n_layers; ++l) {
     if (!w->wqkv[l] || !w->wo[l] || !w->w_gate_up[l] || !w->w_down[l] || !w->norm_attn[l] || !w->norm_mlp[l])
@@ -327,7 +327,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
       gemm_out_elems(p_gu, M, 2 * ff) > c->gemm_out_floats || gemm_out_elems(p_dn, M, d) > c->gemm_out_floats)
     return ESP_ECAPACITY;
   const AttnPlan ap = attn_plan(blk->batch, blk->rows_per_seq, hq, hkv, kv->len_bound);
-  if (attn_partial_floats(blk->batch, blk->rows_per_seq, hq, hd, ap.nsplit) > c->attn_part_floats)
+  if (attn_partial_floats(dt, blk->batch, blk->rows_per_seq, hq, hkv, hd, ap.nsplit) > c->attn_part_floats)
     return ESP_ECAPACITY;
   // the LM-head passes below need an unsplit plan (their epilogues see whole rows): refuse before
   // anything is launched, so that no K/V has been appended when the call fails
@@ -350,7 +350,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     { ESP_PROF(ESP_SITE_ATTN);
       ESP_HIP(launch_attn(s, dt, bd, kd, l, hq, hkv, hd, c->q, c->attn_part, ap)); }
     { ESP_PROF(ESP_SITE_ATTN_MERGE);
-      ESP_HIP(launch_attn_merge(s, dt, bd, kd, hq, hd, c->attn_part, ap, c->attn_out)); }
+      ESP_HIP(launch_attn_merge(s, dt, bd, kd, hq, hkv, hd, c->attn_part, ap, c->attn_out)); }
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
       ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
@@ -625,13 +625,14 @@ esp_status esp_attn_tree(esp_ctx* c, const esp_block* blk, const esp_kv* kv, int
   if (layer < 0 || layer >= c->m.n_layers) return ESP_EINVAL;
   const esp_model_desc& m = c->m;
   const AttnPlan ap = attn_plan(blk->batch, blk->rows_per_seq, m.n_q_heads, m.n_kv_heads, kv->len_bound);
-  if (attn_partial_floats(blk->batch, blk->rows_per_seq, m.n_q_heads, m.head_dim, ap.nsplit) > c->attn_part_floats)
+  if (attn_partial_floats(m.dtype, blk->batch, blk->rows_per_seq, m.n_q_heads, m.n_kv_heads, m.head_dim, ap.nsplit) >
+      c->attn_part_floats)
     return ESP_ECAPACITY;
   { ESP_PROF(ESP_SITE_ATTN);
     ESP_HIP(launch_attn(c->stream, m.dtype, to_dev(blk), to_dev(kv), layer, m.n_q_heads, m.n_kv_heads, m.head_dim, q,
                         c->attn_part, ap)); }
   { ESP_PROF(ESP_SITE_ATTN_MERGE);
-    ESP_HIP(launch_attn_merge(c->stream, m.dtype, to_dev(blk), to_dev(kv), m.n_q_heads, m.head_dim, c->attn_part, ap,
+    ESP_HIP(launch_attn_merge(c->stream, m.dtype, to_dev(blk), to_dev(kv), m.n_q_heads, m.n_kv_heads, m.head_dim, c->attn_part, ap,
                               out)); }
   return ESP_OK;
 }

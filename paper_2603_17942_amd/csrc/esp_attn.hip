@@ -99,62 +99,31 @@ __global__ __launch_bounds__(64) void k_attn_generic(BlockDev b, KvDev kv, int l
 }
 
 // --------------------------------------------------------------------------------------------------
+// k_attn_ring: the bf16 / head_dim 128 kernel.
+//
+// One workgroup per CU owns up to 384 query columns (query row x head of one kv group; a wave per
+// 32 columns, 4 to 12 waves, so two to three waves share a SIMD and the softmax arithmetic of one
+// overlaps the matrix work of another) and one split of the key range.  K/V tiles of 64 keys
+// (16 KB + 16 KB, already in fragment order in the cache) go from global memory straight into a
+// ring of four LDS stages (no register hop, up to three tiles in flight) and are shared by all the
+// waves.  S^T = K Q^T and O^T = V^T P^T both run on v_mfma_f32_32x32x16_bf16: computing the
+// transposed scores leaves each lane with one query column and 16 keys per 32-key block, which is
+// exactly the B-operand layout P^T needs, so the probabilities never leave registers.  Online
+// softmax in fp32 (base-2 exponent), one exchange between the two lane halves per 32 keys.
+// Partial (m, l, O) per split are merged by k_attn_merge in split order (fixed, so results do not
+// depend on scheduling).
 constexpr int K_TILE_BYTES = 64 * 128 * 2;   // 64 keys: two cache blocks of 32 slots, 16 fragments of 1 KB
 constexpr int V_TILE_BYTES = 64 * 128 * 2;
-
-// Tile staging: a tile of 64 keys is 16 KB of K and 16 KB of V, both contiguous in the cache and
-// already in fragment order, so staging is a linear copy.  Loads are unconditional (a piece index
-// past the tile is clamped and its value dropped at the store) so the staging registers stay in
-// VGPRs.
-template <int W>
-__device__ __forceinline__ void attn_load_tile(const bf16_t* __restrict__ kt, const bf16_t* __restrict__ vt, int tid,
-                                               u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
-                                               u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
-  constexpr int NT = 64 * W, PIECES = (1024 + NT - 1) / NT;
-#pragma unroll
-  for (int i = 0; i < PIECES; ++i) {
-    int p = min(tid + NT * i, 1023);
-    kreg[i] = *reinterpret_cast<const u32x4_t*>(kt + (size_t)p * 8);
-    vreg[i] = *reinterpret_cast<const u32x4_t*>(vt + (size_t)p * 8);
-  }
-}
-
-template <int W, bool LAST>
-__device__ __forceinline__ void attn_store_pieces(unsigned char* ks, unsigned char* vs, int tid, int keys_left,
-                                                  const u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
-                                                  const u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
-  constexpr int NT = 64 * W, PIECES = (1024 + NT - 1) / NT;
-#pragma unroll
-  for (int i = 0; i < PIECES; ++i) {
-    int p = tid + NT * i;
-    if (1024 % NT == 0 || p < 1024) {
-      *reinterpret_cast<u32x4_t*>(ks + p * 16) = kreg[i];
-      u32x4_t v = vreg[i];
-      if (LAST) {
-        // piece p = fragment (block p/512, key-step (p/64)%2) of lane p%64; word w holds elements
-        // 2w, 2w+1 = keys k0, k0+1
-        const int kbase = (p >> 9) * 32 + ((p >> 6) & 1) * 16 + ((p >> 5) & 1) * 4;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const int k0 = kbase + 8 * (w >> 1) + 2 * (w & 1);
-          v[w] &= k0 + 1 < keys_left ? 0xffffffffu : (k0 < keys_left ? 0x0000ffffu : 0u);
-        }
-      }
-      *reinterpret_cast<u32x4_t*>(vs + p * 16) = v;
-    }
-  }
-}
-
-// keys_left: keys of the tile that belong to the sequence; V of the others is zeroed (their
-// probability is zero, but 0 * NaN from never-written cache memory would poison the MFMA).
-// Only the last tile of a sequence takes that path (one uniform branch).
-template <int W>
-__device__ __forceinline__ void attn_store_tile(unsigned char* ks, unsigned char* vs, int tid, int keys_left,
-                                                const u32x4_t (&kreg)[(1024 + 64 * W - 1) / (64 * W)],
-                                                const u32x4_t (&vreg)[(1024 + 64 * W - 1) / (64 * W)]) {
-  if (keys_left < 64) attn_store_pieces<W, true>(ks, vs, tid, keys_left, kreg, vreg);
-  else attn_store_pieces<W, false>(ks, vs, tid, keys_left, kreg, vreg);
-}
+constexpr int RING_STAGES = 4;
+constexpr int STAGE_BYTES = K_TILE_BYTES + V_TILE_BYTES;
+constexpr int RING_LDS_BYTES = RING_STAGES * STAGE_BYTES;
+constexpr int RING_MAX_WAVES = 12;
+// The reference m of a column's exponents follows its running maximum lazily: it is set by the first
+// unit that has a visible key and moves only when a score exceeds it by more than this many powers of
+// two, so the output accumulators are rescaled a few times per split instead of at almost every unit.
+// Probabilities may reach 2^RESCALE_SLACK, which fp32 sums and the bf16 operand of the P V product
+// hold without loss of relative precision.
+constexpr float RESCALE_SLACK = 24.0f;
 
 // Visibility bits of 64 consecutive keys for one block row: bit j stands for block position
 // c_lo + j (negative positions are committed cache slots, always visible; positions from
@@ -176,23 +145,142 @@ __device__ __forceinline__ uint64_t key_window(const uint64_t* __restrict__ anc,
   return wnd;
 }
 
-template <int W>
-__global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, int layer, int hq, int hkv,
-                                                      const bf16_t* __restrict__ q, float* __restrict__ part_o,
-                                                      float* __restrict__ part_ml, int nsplit, int tps,
-                                                      int q_tiles) {
-  constexpr int HD = 128;
-  constexpr int NT = 64 * W;
-  constexpr int PIECES = (1024 + NT - 1) / NT;   // 16-byte pieces per thread and tile, K and V alike
-  extern __shared__ __align__(16) unsigned char lds[];
-  unsigned char* ks = lds;                       // [2][K_TILE_BYTES]
-  unsigned char* vs = lds + 2 * K_TILE_BYTES;    // [2][V_TILE_BYTES]
+// zeroes, in the LDS copy of the sequence's last tile, the V entries of keys past its end (their
+// probability is zero, but 0 * NaN from never-written cache memory would poison the accumulators)
+__device__ __forceinline__ void ring_zero_tail(unsigned char* vs, int keys_left, int tid, int nthreads) {
+  for (int p = tid; p < 1024; p += nthreads) {
+    u32x4_t v = *reinterpret_cast<u32x4_t*>(vs + p * 16);
+    // piece p = fragment (block p/512, key-step (p/64)%2) of lane p%64; word w holds elements
+    // 2w, 2w+1 = keys k0, k0+1
+    const int kbase = (p >> 9) * 32 + ((p >> 6) & 1) * 16 + ((p >> 5) & 1) * 4;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int k0 = kbase + 8 * (w >> 1) + 2 * (w & 1);
+      v[w] &= k0 + 1 < keys_left ? 0xffffffffu : (k0 < keys_left ? 0x0000ffffu : 0u);
+    }
+    *reinterpret_cast<u32x4_t*>(vs + p * 16) = v;
+  }
+}
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 31, lg = lane >> 5;
+// max of a value with the value held by the lane 32 places away (the other half of the wave holds the
+// other 16 keys of the same column): one v_permlane32_swap (swaps the upper half of its first operand
+// with the lower half of its second; given the value twice, each result holds one half's values in
+// both halves) instead of a round trip through the LDS crossbar
+__device__ __forceinline__ float max_across_halves(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// One unit of 32 keys for the wave's 32 columns: scores, online softmax, P V.
+// kst / vst: this lane's 16 bytes of the unit's first K fragment (step s at + s KB) and first V
+// fragment ((db, u) at + (db * 2 + u) KB).  vis: visibility bits of this lane's 16 keys at bit
+// 8 (v / 4) + v % 4 (register v <-> key 8 (v / 4) + 4 half + v % 4), used when `masked` (wave-uniform).
+__device__ __forceinline__ void ring_unit(bool masked, const unsigned char* kst, const unsigned char* vst, unsigned vis, float scale,
+                                          const bf16x8_t (&qf)[8], f32x16_t (&oacc)[4], float& m, float& l) {
+  f32x16_t sc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+  // fragment reads run one step ahead of their MFMA and are pinned there (scheduling barriers): left
+  // to itself the compiler hoists all of them and runs out of registers
+  // the matrix phases run at raised wave priority: of the waves that share a SIMD, one with matrix
+  // work issues first and the others fill the gaps with their softmax arithmetic
+  // (the LDS answers after three to four MFMA times: PF reads are in flight, as many as the
+  // registers allow)
+  constexpr int PF = 3, NF = PF + 1;
+  bf16x8_t fr[NF];
+  // fragment j of the unit's 16: K steps 0..7, then V fragments in the order (u, db) = j - 8
+  auto frag_at = [&](int j) {
+    return j < 8 ? *reinterpret_cast<const bf16x8_t*>(kst + j * 1024)
+                 : *reinterpret_cast<const bf16x8_t*>(vst + ((((j - 8) & 3) * 2) + ((j - 8) >> 2)) * 1024);
+  };
+#pragma unroll
+  for (int j = 0; j < PF; ++j) fr[j] = frag_at(j);
+  __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    fr[(s + PF) % NF] = frag_at(s + PF);
+    __builtin_amdgcn_sched_barrier(0);
+    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s % NF], qf[s], sc, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_setprio(0);
+  // scores stay unscaled; the scale is folded into the exponent: p = 2^(s*scale - m*scale)
+  if (masked) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sc[v] = ((vis >> (8 * (v >> 2) + (v & 3))) & 1u) ? sc[v] : NEG_BIG;
+  }
+  float tmax = fmaxf(sc[0], sc[1]);
+#pragma unroll
+  for (int v = 2; v < 16; v += 2) tmax = fmaxf(tmax, fmaxf(sc[v], sc[v + 1]));
+  tmax = max_across_halves(tmax);
+  const float m_new = tmax * scale > m * scale + RESCALE_SLACK ? tmax : m;
+  // no key of the column visible so far (m_new at its start value): any finite reference does, the
+  // masked scores' exponents then lie far below the range and their probabilities come out as 0
+  const float mb = m_new > 0.5f * NEG_BIG ? m_new * scale : 0.f;
+  // m still at its start value: nothing accumulated yet, nothing to scale
+  const bool moved = m_new != m && m > 0.5f * NEG_BIG;
+  if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
+    const float alpha = m > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(m * scale - mb) : 1.0f;
+    l *= alpha;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
+  }
+  m = m_new;
+  __builtin_amdgcn_sched_barrier(0);
+  // exponentials four at a time (fenced: all sixteen in flight at once cost registers the Q
+  // fragments need), converted to the bf16 operand fragments as they come
+  float lsum = 0.f;
+  bf16x8_t pf[2];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = 4 * c + e;
+      // a masked score is NEG_BIG: its exponent lies far below the range, p = 0 without a test
+      float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale, -mb));
+      lsum += p;
+      pf[v >> 3][v & 7] = (bf16_t)p;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  l += lsum;
+  __builtin_amdgcn_s_setprio(2);
+  // O^T += V^T P^T: k-step u takes registers 8u..8u+7, i.e. keys 16u + {0, 8} + 4 half + 0..3 -- one
+  // 16-byte read in the permuted LDS order
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {                 // i = u * 4 + db
+    const int u = i >> 2, db = i & 3;
+    if (i + PF < 8) fr[(8 + i + PF) % NF] = frag_at(8 + i + PF);
+    __builtin_amdgcn_sched_barrier(0);
+    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[(8 + i) % NF], pf[u], oacc[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
+// LPW: 1 KB wave-loads per loading wave and tile (the first 32 / LPW waves of the workgroup load)
+template <int LPW>
+__global__ __launch_bounds__(64 * RING_MAX_WAVES) void k_attn_ring(BlockDev b, KvDev kv, int layer, int hq, int hkv,
+                                                                  const bf16_t* __restrict__ q,
+                                                                  float* __restrict__ part_o,
+                                                                  float* __restrict__ part_ml, int nsplit, int tps,
+                                                                  int q_tiles, int ct_wg, int n_full) {
+  constexpr int HD = 128;
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lg = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // this wave's column tile inside the workgroup and the halves of every key tile it works on: waves
+  // up to n_full take a whole tile each, the others pair up on one (first = keys 0..31 of a tile,
+  // second = keys 32..63) and are merged at the end; waves beyond the tiles only help load
+  const int ctl = wave < n_full ? wave : n_full + ((wave - n_full) >> 1);
+  const bool pair = wave >= n_full;
+  const int kh_first = pair ? ((wave - n_full) & 1) : 0, kh_last = pair ? kh_first : 1;
   const int G = hq / hkv;
-  // XCD-aware logical id (hardware ids go round-robin over the 8 XCDs): the query tiles that
-  // stream the same keys (same kv head, same split) get consecutive logical ids on one XCD and
-  // so share its L2.
+  // XCD-aware logical id: the query tiles that stream the same keys (same kv head, same split) get
+  // consecutive logical ids on one XCD and so share its L2
   const int total_wg = q_tiles * hkv * b.batch * nsplit;
   const int per_xcd = (total_wg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -203,42 +291,80 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
   const int seq = zz / nsplit, sp = zz % nsplit;
   const int nr = b.n_rows[seq];
   if (!seq_ok(kv, seq, nr, b.rows_per_seq)) return;
-  if (qt * (W * 32) >= nr * G) return;                  // no live query column in this workgroup
+  const int ncols = nr * G;
+  if (qt * ct_wg * 32 >= ncols) return;                 // no live query column in this workgroup
   const int L = kv.len[seq], total = L + nr;
   const int ntiles = (total + 63) >> 6;
   const int t0 = sp * tps, t1 = min(ntiles, t0 + tps);
+  const int nt = t1 - t0;
 
-  const int qcol = (qt * W + wave) * 32 + lr;
-  const bool col_live = qcol < nr * G;
+  const int qcol = (qt * ct_wg + ctl) * 32 + lr;
+  const bool col_live = qcol < ncols;
+  const bool wave_live = ctl < ct_wg && (qt * ct_wg + ctl) * 32 < ncols;  // wave-uniform
   const int r = col_live ? qcol / G : 0;
   const int h = kvh * G + (col_live ? qcol % G : 0);
   const size_t row = (size_t)seq * b.rows_per_seq + r;
-  const size_t item = (row * hq + h) * nsplit + sp;
+  // partial of this wave's column tile and split: O^T as [feature][column] (a store instruction of
+  // the wave covers whole 128-byte lines), then (m, l) per column
+  const size_t ptile = (((size_t)seq * hkv + kvh) * (q_tiles * ct_wg) + qt * ct_wg + min(ctl, ct_wg - 1)) * nsplit + sp;
+  float* po = part_o + ptile * (HD * 32);
+  float* pml = part_ml + ptile * 64;
 
-  if (t0 >= t1) {   // empty split: neutral partial
-    if (col_live) {
-      f32x4_t z = {0.f, 0.f, 0.f, 0.f};
-      for (int i = lg; i < 32; i += 2) *reinterpret_cast<f32x4_t*>(part_o + item * HD + 4 * i) = z;
-      if (lg == 0) { part_ml[item * 2] = NEG_BIG; part_ml[item * 2 + 1] = 0.f; }
+  if (nt <= 0) {   // empty split: neutral partial
+    if (wave_live && kh_first == 0) {
+      for (int f = lg; f < HD; f += 2) po[f * 32 + lr] = 0.f;
+      if (lg == 0) { pml[lr * 2] = NEG_BIG; pml[lr * 2 + 1] = 0.f; }
     }
     return;
   }
 
-  // Q^T fragments: lane = query column, 8 features per k-step at 16*s + 8*lg
+  // ---- ring: tile i of the split lives in stage i % 4; piece p of a tile (1 KB) is K piece p for
+  // p < 16, V piece p - 16 otherwise; loading wave w brings pieces w * LPW .. w * LPW + LPW - 1
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+  const bool loader = wave < 32 / LPW;
+  const int64_t base = kv.base[seq];
+  const unsigned char* kt0 =
+      reinterpret_cast<const unsigned char*>((const bf16_t*)kv.k + kv_plane(layer, kvh, hkv, kv.capacity, HD) + (size_t)base * HD);
+  const unsigned char* vt0 =
+      reinterpret_cast<const unsigned char*>((const bf16_t*)kv.v + kv_plane(layer, kvh, hkv, kv.capacity, HD) + (size_t)base * HD);
+  const int piece0 = wave * LPW;                        // wave-uniform
+  const unsigned char* src0 = (piece0 < 16 ? kt0 : vt0) + (size_t)(piece0 & 15) * 1024;
+  const uint32_t lane_off = (uint32_t)lane * 16;
+  auto issue_tile = [&](int i) {
+    if (!loader) return;
+    const unsigned char* src = src0 + (size_t)(t0 + i) * K_TILE_BYTES;
+    const uint32_t dst = lds0 + (i & 3) * STAGE_BYTES + piece0 * 1024;
+    load_to_lds16_sbase<0>(src, lane_off, dst);
+    load_to_lds16_sbase<1024>(src, lane_off, dst);
+    load_to_lds16_sbase<2048>(src, lane_off, dst);
+    load_to_lds16_sbase<3072>(src, lane_off, dst);
+    if (LPW == 8) {
+      load_to_lds16_sbase<0>(src + 4096, lane_off, dst + 4096);
+      load_to_lds16_sbase<1024>(src + 4096, lane_off, dst + 4096);
+      load_to_lds16_sbase<2048>(src + 4096, lane_off, dst + 4096);
+      load_to_lds16_sbase<3072>(src + 4096, lane_off, dst + 4096);
+    }
+  };
+  // Q^T fragments: lane = query column, 8 features per k-step at 16 s + 8 lg.  The compiler places
+  // waits on the load counter for the loads it knows of, and one of those inside the tile loop would
+  // also drain the ring's prefetches (which it does not know of).  So the fragments are loaded
+  // between the first tile's loads and the others', and an empty statement that names them right
+  // after makes the compiler wait for them here: by then the first tile (older, loads retire in
+  // order) has landed too, which the first iteration needs anyway, and no load of the compiler's is
+  // left in flight when the loop starts.
+  issue_tile(0);
   bf16x8_t qf[8];
   {
     const bf16_t* qp = q + (row * hq + h) * HD + 8 * lg;
 #pragma unroll
     for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * s);
+    asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7])
+                 :: "memory");
   }
+  if (nt > 1) issue_tile(1);
+  if (nt > 2) issue_tile(2);
   const uint64_t* anc = b.anc + row * b.anc_words;
-  const bf16_t* kp = (const bf16_t*)kv.k + kv_plane(layer, kvh, hkv, kv.capacity, HD);
-  const bf16_t* vp = (const bf16_t*)kv.v + kv_plane(layer, kvh, hkv, kv.capacity, HD);
-  const int64_t base = kv.base[seq];
   const float scale = LOG2E / sqrtf((float)HD);
-
-  u32x4_t kreg[PIECES], vreg[PIECES];
-
   f32x16_t oacc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -246,150 +372,66 @@ __global__ __launch_bounds__(64 * W, 2) void k_attn_mfma(BlockDev b, KvDev kv, i
     for (int v = 0; v < 16; ++v) oacc[i][v] = 0.f;
   float m = NEG_BIG, l = 0.f;
 
-  // tile t of K and of V: 64 * HD elements each, contiguous (two cache blocks)
-  const bf16_t* kt0 = kp + (size_t)base * HD;
-  const bf16_t* vt0 = vp + (size_t)base * HD;
-  attn_load_tile<W>(kt0 + (size_t)t0 * 64 * HD, vt0 + (size_t)t0 * 64 * HD, tid, kreg, vreg);
-  attn_store_tile<W>(ks, vs, tid, total - t0 * 64, kreg, vreg);
-  __syncthreads();
-
-  for (int t = t0; t < t1; ++t) {
-    const int buf = (t - t0) & 1;
-    const bool more = t + 1 < t1;
-    {
-      const int tn = more ? t + 1 : t;
-      attn_load_tile<W>(kt0 + (size_t)tn * 64 * HD, vt0 + (size_t)tn * 64 * HD, tid, kreg, vreg);
-    }
-
-    // S^T = K Q^T for the two 32-key blocks of the tile.  The MFMA phases run at raised wave
-    // priority: of the two waves that share a SIMD, the one with matrix work issues first and the
-    // other fills the gaps with its softmax arithmetic.
-    __builtin_amdgcn_s_setprio(2);
-    f32x16_t sacc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[kb][v] = 0.f;
-    // Fragment reads run one group (4 reads, 4 MFMAs) ahead of their use and are pinned there by
-    // scheduling barriers: left to itself the compiler funnels every read through one register
-    // quad and waits out the full LDS latency before each MFMA.
-    const unsigned char* kbase = ks + buf * K_TILE_BYTES + lane * 16;   // fragment (kb, s) at (kb*8 + s) KB
-    bf16x8_t fr[2][4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)   // group g holds steps 2g, 2g+1 of both key blocks: j = 2*(s&1) + kb
-      fr[0][j] = *reinterpret_cast<const bf16x8_t*>(kbase + ((j & 1) * 8 + (j >> 1)) * 1024);
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      if (g < 3) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          fr[(g + 1) & 1][j] =
-              *reinterpret_cast<const bf16x8_t*>(kbase + ((j & 1) * 8 + 2 * (g + 1) + (j >> 1)) * 1024);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        sacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[2 * g + (j >> 1)], sacc[j & 1], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // register v of block kb <-> key kb*32 + 8*(v/4) + 4*lg + v%4.  Scores stay unscaled; the
-    // scale is folded into the exponent: p = 2^(s*scale - m*scale).
-    const int key0 = t * 64;
-    const bool masked_tile = key0 + 64 > L;   // tiles inside the committed cache need no mask
-    if (masked_tile) {
-      // visibility of the tile's 64 keys for this lane's row, bit j <-> key key0 + j
-      const uint64_t wnd = key_window(anc, b.anc_words, key0 - L, total - key0);
-      const unsigned wlo = (unsigned)wnd >> (4 * lg), whi = (unsigned)(wnd >> 32) >> (4 * lg);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const unsigned bit = ((kb ? whi : wlo) >> (8 * (v >> 2) + (v & 3))) & 1u;
-          sacc[kb][v] = bit ? sacc[kb][v] : NEG_BIG;
-        }
-    }
-    __builtin_amdgcn_s_setprio(0);
-    float tmax = NEG_BIG;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][v]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m, tmax);
-    const float mb = m_new * scale;
-    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0ull) {   // rescale only when some column's max moved
-      const float alpha = __builtin_amdgcn_exp2f(m * scale - mb);
-      l *= alpha;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[i][v] *= alpha;
-    }
-    m = m_new;
-    float lsum = 0.f;
-    if (masked_tile) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float sv = sacc[kb][v];
-          float p = sv > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(fmaf(sv, scale, -mb)) : 0.f;
-          sacc[kb][v] = p;
-          lsum += p;
-        }
-    } else {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][v], scale, -mb));
-          sacc[kb][v] = p;
-          lsum += p;
-        }
-    }
-    l += lsum;
-
-    // O^T += V^T P^T: k-step (kb, u) takes registers 8u..8u+7 of block kb, i.e. keys
-    // kb*32 + 16u + {0, 8} + 4*lg + 0..3 -- one 16-byte read in the permuted LDS order
-    __builtin_amdgcn_s_setprio(2);
-    const unsigned char* vbase = vs + buf * V_TILE_BYTES + lane * 16;   // fragment (kb, db, u) at (kb*8 + db*2 + u) KB
-#pragma unroll
-    for (int db = 0; db < 4; ++db) fr[0][db] = *reinterpret_cast<const bf16x8_t*>(vbase + db * 2048);
-#pragma unroll
-    for (int ku = 0; ku < 4; ++ku) {   // k-step ku = 2*kb + u
-      if (ku < 3) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-          fr[(ku + 1) & 1][db] =
-              *reinterpret_cast<const bf16x8_t*>(vbase + (((ku + 1) >> 1) * 8 + db * 2 + ((ku + 1) & 1)) * 1024);
-      }
-      bf16x8_t pf;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) pf[j] = (bf16_t)sacc[ku >> 1][8 * (ku & 1) + j];
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ku & 1][db], pf, oacc[db], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __builtin_amdgcn_s_setprio(0);
-    if (more)
-      attn_store_tile<W>(ks + (buf ^ 1) * K_TILE_BYTES, vs + (buf ^ 1) * V_TILE_BYTES, tid, total - (t + 1) * 64, kreg,
-                         vreg);
+  const unsigned char* frag = lds + lane * 16;          // this lane's 16 bytes of fragment 0 of stage 0
+  for (int i = 0; i < nt; ++i) {
+    // tile i has landed (this wave's loads: they retire in order and the tiles after i stay in
+    // flight; the barrier covers the other waves'); every wave is done with tile i - 1, whose stage
+    // takes tile i + 3
+    if (i + 2 < nt) wait_loads_but<2 * LPW>();
+    else if (i + 1 < nt) wait_loads_but<LPW>();
+    else wait_loads_but<0>();
     __syncthreads();
+    if (i + 3 < nt) issue_tile(i + 3);
+    const int key0 = (t0 + i) * 64;
+    const int keys_left = total - key0;
+    if (keys_left < 64) {
+      ring_zero_tail(lds + (i & 3) * STAGE_BYTES + K_TILE_BYTES, keys_left, tid, blockDim.x);
+      __syncthreads();
+    }
+    if (!wave_live) continue;
+    const unsigned char* st = frag + (i & 3) * STAGE_BYTES;
+    const bool masked = key0 + 64 > L;                   // the tile touches the block rows or the sequence's end
+    uint64_t wnd = 0;
+    if (masked) wnd = key_window(anc, b.anc_words, key0 - L, keys_left);
+    if (kh_first == 0) ring_unit(masked, st, st + K_TILE_BYTES, (unsigned)wnd >> (4 * lg), scale, qf, oacc, m, l);
+    if (kh_last == 1)
+      ring_unit(masked, st + 8192, st + K_TILE_BYTES + 8192, (unsigned)(wnd >> 32) >> (4 * lg), scale, qf, oacc, m, l);
   }
 
   l += __shfl_xor(l, 32, 64);
-  if (col_live) {
+  if (n_full < ct_wg) {
+    // paired waves: the second hands its (m, l, O) to the first through LDS (the ring is free now)
+    __syncthreads();
+    float* xo = reinterpret_cast<float*>(lds) + (size_t)(ctl - n_full) * (HD * 32 + 64);
+    if (pair && kh_first == 1 && wave_live) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xo[(db * 16 + v) * 64 + lane] = oacc[db][v];
+      if (lg == 0) { xo[HD * 32 + lr * 2] = m; xo[HD * 32 + lr * 2 + 1] = l; }
+    }
+    __syncthreads();
+    if (pair && kh_first == 0 && wave_live) {
+      const float mo = xo[HD * 32 + lr * 2], lo = xo[HD * 32 + lr * 2 + 1];
+      const float mm = fmaxf(m, mo);
+      // a side that saw no visible key (m at its start value) holds nothing: weight it out
+      const float wa = m > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f((m - mm) * scale) : 0.f;
+      const float wb = mo > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f((mo - mm) * scale) : 0.f;
+      l = l * wa + lo * wb;
+      m = mm;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[db][v] = oacc[db][v] * wa + xo[(db * 16 + v) * 64 + lane] * wb;
+    }
+  }
+  if (wave_live && kh_first == 0) {
     // register v of feature block db <-> feature db*32 + 8*(v/4) + 4*lg + v%4
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        f32x4_t o4 = {oacc[db][4 * vq], oacc[db][4 * vq + 1], oacc[db][4 * vq + 2], oacc[db][4 * vq + 3]};
-        *reinterpret_cast<f32x4_t*>(part_o + item * HD + db * 32 + 8 * vq + 4 * lg) = o4;
-      }
-    if (lg == 0) { part_ml[item * 2] = m * scale; part_ml[item * 2 + 1] = l; }   // m in the exponent's units
+      for (int v = 0; v < 16; ++v) po[(db * 32 + 8 * (v >> 2) + 4 * lg + (v & 3)) * 32 + lr] = oacc[db][v];
+    if (lg == 0) { pml[lr * 2] = m * scale; pml[lr * 2 + 1] = l; }   // m in the exponent's units
   }
 }
 
@@ -434,26 +476,147 @@ __global__ __launch_bounds__(256) void k_attn_merge(BlockDev b, KvDev kv, int hq
   store4(dst, acc * inv);
 }
 
+// Merge for the ring kernel's partial layout ([column tile][split][feature][column]), in split
+// order.  A workgroup of 256 threads takes 32 features of one column tile of 32 query columns.
+// First the weights 2^(m_s - max) of the tile's columns and splits: thread (split group, column)
+// fetches the (m, l) of every eighth split at once -- one after the other, a column's splits would
+// cost a memory latency each -- and the eight groups combine through LDS.  Then thread (column,
+// feature quad) sums the splits' O, every load instruction of a wave covering whole 128-byte lines.
+template <int MAXS>
+__global__ __launch_bounds__(256) void k_attn_merge_ring(BlockDev b, KvDev kv, int hq, int hkv,
+                                                         const float* __restrict__ part_o,
+                                                         const float* __restrict__ part_ml, int nsplit,
+                                                         int n_ct, bf16_t* __restrict__ out) {
+  constexpr int HD = 128, PER = MAXS / 8;
+  __shared__ float w_s[MAXS][32];
+  __shared__ float red[8][32];
+  __shared__ float red_l[8][32];
+  const int G = hq / hkv;
+  const int fq = blockIdx.x & 3;
+  const int tile = blockIdx.x >> 2;                 // (seq * hkv + kvh) * n_ct + ct
+  const int ct = tile % n_ct, kvh = (tile / n_ct) % hkv, seq = tile / (n_ct * hkv);
+  const int nr = b.n_rows[seq];
+  const bool ok = seq_ok(kv, seq, nr, b.rows_per_seq);
+  const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int c = ct * 32 + col;                      // column within the kv group
+  const bool in_block = c < b.rows_per_seq * G;     // has an output row at all
+  const bool live = ok && c < nr * G;
+  const size_t t0 = (size_t)tile * nsplit;
+  float ms[PER], ls[PER];
+  float mx = NEG_BIG;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int sp = grp + 8 * i;
+    ms[i] = NEG_BIG; ls[i] = 0.f;
+    if (live && sp < nsplit) {
+      const float2 ml = *reinterpret_cast<const float2*>(part_ml + (t0 + sp) * 64 + col * 2);
+      ms[i] = ml.x; ls[i] = ml.y;
+    }
+    mx = fmaxf(mx, ms[i]);
+  }
+  red[grp][col] = mx;
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < 8; ++g) mx = fmaxf(mx, red[g][col]);
+  float lt = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int sp = grp + 8 * i;
+    const float w = exp2f(ms[i] - mx);
+    if (sp < nsplit) w_s[sp][col] = w;
+    lt += ls[i] * w;
+  }
+  red_l[grp][col] = lt;
+  __syncthreads();
+  if (!in_block) return;
+  // the splits' sums are added in group order: fixed, like everything else here
+  lt = 0.f;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) lt += red_l[g][col];
+  const float inv = lt > 0.f ? 1.f / lt : 0.f;
+  const int fsub = grp;
+  const int f0 = fq * 32 + fsub * 4;
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    const float* p = part_o + t0 * (HD * 32) + (size_t)f0 * 32 + col;
+#pragma unroll 8
+    for (int s = 0; s < nsplit; ++s) {
+      const float w = w_s[s][col];
+      const float* ps = p + (size_t)s * (HD * 32);
+      acc[0] += ps[0] * w; acc[1] += ps[32] * w; acc[2] += ps[64] * w; acc[3] += ps[96] * w;
+    }
+    acc *= inv;
+  }
+  const int r = c / G, h = kvh * G + c % G;
+  store4(out + (((size_t)seq * b.rows_per_seq + r) * hq + h) * HD + f0, acc);
+}
+
+}  // namespace
+
+// the ring kernel uses more dynamic LDS than a kernel gets by default: raise the limit once (also
+// called when a context is created, so that no launch inside a stream capture is the first one)
+hipError_t attn_prepare() {
+  static const hipError_t attr = [] {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_ring<4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, RING_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_ring<8>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               RING_LDS_BYTES);
+  }();
+  return attr;
+}
+
+namespace {
+// Geometry of the ring kernel for `cols` query columns per kv head.  A column tile is 32 columns; a
+// workgroup owns ct_wg of them (as few workgroups per kv head and split as twelve waves allow, the
+// tiles spread evenly).  Its first n_full tiles get a wave each; each of the others is worked by two
+// waves, one per half of every key tile, when that evens out the load of the four SIMDs (waves go
+// to SIMDs round-robin, and the SIMD with the most matrix work sets the pace): ct_wg = 9 gives
+// SIMD loads of 5, 5, 4, 4 half-tiles instead of 6, 4, 4, 4.  At least four waves (they carry the loads).
+struct RingGeometry { int q_tiles, ct_wg, n_full, waves; };
+RingGeometry ring_geometry(int cols) {
+  RingGeometry g;
+  const int ct = (cols + 31) / 32;
+  g.q_tiles = (ct + RING_MAX_WAVES - 1) / RING_MAX_WAVES;
+  g.ct_wg = (ct + g.q_tiles - 1) / g.q_tiles;
+  const int rem = g.ct_wg & 3;
+  const int n_split = ((rem == 1 || rem == 2) && g.ct_wg > 4 && g.ct_wg + rem <= RING_MAX_WAVES) ? rem : 0;
+  g.n_full = g.ct_wg - n_split;
+  g.waves = std::max(4, g.n_full + 2 * n_split);
+  return g;
+}
 }  // namespace
 
 AttnPlan attn_plan(int batch, int rows_per_seq, int hq, int hkv, int len_bound) {
-  // Splits of the key range: enough workgroups for ~1.5 per CU, but no more -- every split
-  // writes a partial (m, l, O) per query row and head that the merge kernel reads back -- and
-  // at least 3 key tiles of 64 per split.
+  // Splits of the key range.  A workgroup (one per CU) owns the query columns of one kv head -- or a
+  // share of them when they exceed twelve waves -- and one split; every split writes a partial
+  // (m, l, O) per query row and head that the merge kernel reads back, so: as few splits as fill the
+  // 256 CUs once, no second, mostly empty round, and a few tiles of 64 keys per split at least.
+  // Cost model per candidate: rounds over the CUs times (tiles per split + a fixed per-workgroup
+  // cost of about four tiles).
   AttnPlan p;
-  int nt = (len_bound + rows_per_seq + 63) / 64;
-  int G = hq / hkv;
-  int qtiles = (rows_per_seq * G + 127) / 128;
-  int base = qtiles * hkv * batch;
-  int want = (384 + base - 1) / base;
-  int max_by_len = std::max(1, nt / 3);
-  int ns = std::max(1, std::min(std::min(want, max_by_len), 64));
-  p.tiles_per_split = (nt + ns - 1) / ns;
+  const int nt = (len_bound + rows_per_seq + 63) / 64;
+  const int G = hq / hkv;
+  const int base = ring_geometry(rows_per_seq * G).q_tiles * hkv * batch;
+  int best = 1, best_cost = 1 << 30;
+  for (int ns = 1; ns <= 64; ++ns) {
+    const int tps = (nt + ns - 1) / ns;
+    if (ns > 1 && tps < 2) break;
+    if ((nt + tps - 1) / tps != ns) continue;             // same partition as a smaller count
+    const int rounds = (base * ns + 255) / 256;
+    const int cost = rounds * (tps + 4);
+    if (cost < best_cost) { best_cost = cost; best = ns; }
+  }
+  p.tiles_per_split = (nt + best - 1) / best;
   p.nsplit = (nt + p.tiles_per_split - 1) / p.tiles_per_split;
   return p;
 }
 
-size_t attn_partial_floats(int batch, int rows_per_seq, int hq, int hd, int nsplit) {
+size_t attn_partial_floats(int dtype, int batch, int rows_per_seq, int hq, int hkv, int hd, int nsplit) {
+  if (dtype == ESP_BF16 && hd == 128) {   // ring layout: whole column tiles of 32
+    const RingGeometry g = ring_geometry(rows_per_seq * (hq / hkv));
+    return (size_t)batch * hkv * g.q_tiles * g.ct_wg * nsplit * (32 * (hd + 2));
+  }
   return (size_t)batch * rows_per_seq * hq * nsplit * (hd + 2);
 }
 
@@ -463,30 +626,18 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
   float* part_o = partials;
   float* part_ml = partials + (size_t)M * hq * p.nsplit * hd;
   if (dtype == ESP_BF16 && hd == 128) {
-    const int G = hq / hkv;
-    const int cols = b.rows_per_seq * G;
-    const int wave_tiles = (cols + 31) / 32;
-    // waves per workgroup: 3 or 4, whichever pads the column range less (ties: 4)
-    int W = 4, best_pad = 1 << 30;
-    for (int w = 4; w >= 3; --w) {
-      int pad = ((wave_tiles + w - 1) / w) * w - wave_tiles;
-      if (pad < best_pad) { best_pad = pad; W = w; }
-    }
-    const int q_tiles = (wave_tiles + W - 1) / W;
-    const int total_wg = q_tiles * hkv * b.batch * p.nsplit;
-    dim3 grid(((total_wg + 7) / 8) * 8);
-    size_t lds = 2 * (size_t)(K_TILE_BYTES + V_TILE_BYTES);
-    // 64 KB of dynamic LDS: the default limit, no attribute needed
-#define ESP_ATTN_CASE(w)                                                                                  \
-  case w:                                                                                                 \
-    hipLaunchKernelGGL(k_attn_mfma<w>, grid, dim3(64 * w), lds, st, b, kv, layer, hq, hkv, (const bf16_t*)q, \
-                       part_o, part_ml, p.nsplit, p.tiles_per_split, q_tiles);                            \
-    break;
-    switch (W) {
-      ESP_ATTN_CASE(3)
-      ESP_ATTN_CASE(4)
-    }
-#undef ESP_ATTN_CASE
+    const RingGeometry g = ring_geometry(b.rows_per_seq * (hq / hkv));
+    part_ml = partials + (size_t)b.batch * hkv * g.q_tiles * g.ct_wg * p.nsplit * (32 * hd);
+    const int total_wg = g.q_tiles * hkv * b.batch * p.nsplit;
+    const hipError_t attr = attn_prepare();
+    if (attr != hipSuccess) return attr;
+    const dim3 grid(((total_wg + 7) / 8) * 8), block(64 * g.waves);
+    if (g.waves >= 8)
+      hipLaunchKernelGGL(k_attn_ring<4>, grid, block, RING_LDS_BYTES, st, b, kv, layer, hq, hkv, (const bf16_t*)q, part_o,
+                         part_ml, p.nsplit, p.tiles_per_split, g.q_tiles, g.ct_wg, g.n_full);
+    else
+      hipLaunchKernelGGL(k_attn_ring<8>, grid, block, RING_LDS_BYTES, st, b, kv, layer, hq, hkv, (const bf16_t*)q, part_o,
+                         part_ml, p.nsplit, p.tiles_per_split, g.q_tiles, g.ct_wg, g.n_full);
   } else {
     dim3 grid(M, hq, p.nsplit);
     if (dtype == ESP_F32 && hd == 64)
@@ -504,8 +655,21 @@ hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev
   return hipGetLastError();
 }
 
-hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int hq, int hd,
+hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int hq, int hkv, int hd,
                              const float* partials, const AttnPlan& p, void* out) {
+  if (dtype == ESP_BF16 && hd == 128) {
+    const RingGeometry g = ring_geometry(b.rows_per_seq * (hq / hkv));
+    const int n_ct = g.q_tiles * g.ct_wg;
+    const float* part_o = partials;
+    const float* part_ml = partials + (size_t)b.batch * hkv * n_ct * p.nsplit * (32 * hd);
+    const dim3 grid(b.batch * hkv * n_ct * 4);
+    if (p.nsplit <= 64)
+      hipLaunchKernelGGL(k_attn_merge_ring<64>, grid, dim3(256), 0, st, b, kv, hq, hkv, part_o, part_ml, p.nsplit, n_ct,
+                         (bf16_t*)out);
+    else
+      return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
   const int M = b.batch * b.rows_per_seq;
   const float* part_o = partials;
   const float* part_ml = partials + (size_t)M * hq * p.nsplit * hd;

@@ -38,18 +38,6 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 
 constexpr int A_ROW_BYTES = 144;  // 128 B of bf16 + 16 B pad: conflict-free ds_read_b128 over 8 rows
 
-// One 16-byte piece per lane from global memory straight into LDS (no register hop): the lane
-// supplies its own global address, the wave's 64 pieces land at lds_addr + 16 * lane.  Issued as
-// text so that the compiler's wait-count bookkeeping knows nothing of it: the ring below counts
-// its own loads (they retire in order) and would otherwise be drained before every LDS read.
-__device__ __forceinline__ void load_to_lds16(const void* g, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
-}
-template <int N_YOUNGER>
-__device__ __forceinline__ void wait_loads_but() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_YOUNGER) : "memory");
-}
-
 // EPI: epilogue -- 0 fp32 tile out, 1 per-row arg-max over the workgroup's columns (pairs to out),
 // 2 SwiGLU of interleaved gate/up column blocks to bf16, 3 fp32 tile to out and arg-max pairs to out2
 // RING > 0 (packed weights only): both operands ride a ring of RING chunk stages in LDS, filled

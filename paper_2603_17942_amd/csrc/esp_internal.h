@@ -34,6 +34,39 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// ---- direct global -> LDS loads --------------------------------------------------------------
+// One 16-byte piece per lane from global memory straight into LDS (no register hop): the lane
+// supplies its own global address, the wave's 64 pieces land at lds_addr + 16 * lane.  Issued as
+// text so that the compiler's wait-count bookkeeping knows nothing of it: the LDS rings of the GEMM
+// and attention kernels count their own loads (they retire in order) and would otherwise be
+// drained before every LDS read.
+// M0 (the LDS base of the transfer) is put back to what it held before, so the statement leaves no
+// register changed that the compiler might rely on.
+__device__ __forceinline__ void load_to_lds16(const void* g, uint32_t lds_addr) {
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "s"(lds_addr), "v"(g)
+               : "memory");
+}
+// The same with a wave-uniform base address (scalar registers) plus a per-lane byte offset and a
+// constant offset IMM, which the hardware adds to the global address and to the LDS address alike
+// (piece j of a run: IMM = j KB, lds_addr the address of piece 0): one vector register for any
+// number of pieces.
+template <int IMM>
+__device__ __forceinline__ void load_to_lds16_sbase(const void* sbase, uint32_t lane_off, uint32_t lds_addr) {
+  uint32_t keep;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 offset:%4\n\ts_mov_b32 m0, %0"
+      : "=&s"(keep)
+      : "s"(lds_addr), "v"(lane_off), "s"(sbase), "n"(IMM)
+      : "memory");
+}
+template <int N_YOUNGER>
+__device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_YOUNGER) : "memory");
+}
+
 // ---- sample matching (temperature 1): counter-based Gumbel noise ---------------------------------
 // u in (0,1) from a 32-bit multiply-xorshift mix (MurmurHash3 finaliser family) of (seed, position,
 // token id), top 23 bits centred in their cell (exact in fp32); g = -ln(-ln u) is standard Gumbel, and
@@ -143,10 +176,11 @@ hipError_t launch_mask_ema(hipStream_t st, int dtype, const void* embed, const i
 // ---- attention (esp_attn.hip) ------------------------------------------------------------------
 struct AttnPlan { int nsplit; int tiles_per_split; };
 AttnPlan attn_plan(int batch, int rows_per_seq, int hq, int hkv, int len_bound);
-size_t attn_partial_floats(int batch, int rows_per_seq, int hq, int hd, int nsplit);
+hipError_t attn_prepare();   // one-time kernel attributes (dynamic LDS limit)
+size_t attn_partial_floats(int dtype, int batch, int rows_per_seq, int hq, int hkv, int hd, int nsplit);
 hipError_t launch_attn(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer, int hq,
                        int hkv, int hd, const void* q, float* partials, const AttnPlan& p);
-hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int hq, int hd,
+hipError_t launch_attn_merge(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int hq, int hkv, int hd,
                              const float* partials, const AttnPlan& p, void* out);
 
 // ---- softmax + top-k (esp_topk.hip) -----------------------------------------------------------
