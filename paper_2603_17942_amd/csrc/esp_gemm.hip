@@ -6,20 +6,24 @@
 //    K-chunk is stored as [step][lane][8 values] = 4 KB contiguous in MFMA B-operand order, so every
 //    wave-wide load covers 1 KB of consecutive addresses and the data goes HBM -> VGPR -> MFMA with no
 //    LDS hop.  Tiles are ordered chunk-major ([chunk][row block]): at any moment the waves of the
-//    whole grid, which advance through the chunks together, read one contiguous window of HBM.  Inside a chunk the k index is permuted identically for both operands (lane group g,
-//    step s holds k = 32 g + 8 s + 0..7), which leaves the dot product unchanged.
-//  * Large tiles (>= 8 MFMA tiles per wave, one wave per SIMD; k_gemm_bf16_ring): both operands go
-//    global -> LDS directly (global_load_lds_dwordx4, no register hop) into a ring of three chunk
-//    stages that fills all but 4 KB of the CU's LDS; the loads of chunk c+2 are issued between the
-//    MFMA groups of chunk c.  Smaller tiles keep the operands in register rings:
+//    whole grid, which advance through the chunks together, read one contiguous window of HBM.
+//    Inside a chunk the k index is permuted identically for both operands (lane group g, step s
+//    holds k = 32 g + 8 s + 0..7), which leaves the dot product unchanged.
+//  * Large tiles (>= 8 MFMA tiles per wave; k_gemm_bf16_ring): both operands go global -> LDS
+//    directly (global_load_lds_dwordx4, no register hop) into a ring of three chunk stages that
+//    fills all but 4 KB of the CU's LDS.  Four computing waves (one per SIMD) only read fragments
+//    and issue MFMAs; four loading waves (the second wave of each SIMD) issue the loads of chunk
+//    c+2 while chunk c is computed.  Smaller tiles keep the operands in register rings:
 //  * A register ring keeps D chunks of weights in flight per wave.  The activations of a chunk (L2
 //    resident, shared by the four waves through LDS) ride in a ring of the same depth and are issued
 //    together with the weights of the same chunk: loads retire in order, so waiting for the
 //    activations of chunk c+1 leaves the D-2 younger chunks of the weight stream in flight.
 //  * v_mfma_f32_32x32x16_bf16, fp32 accumulation; LDS fragment reads are double-buffered one MFMA
 //    step ahead.
-//  * Split-K (grid z) depends on (N, K) only and partial sums are reduced by the consumer in split
-//    order, so a row's result does not depend on how many other rows the block holds.
+//  * Split-K (grid z): partial sums are reduced by the consumer in split order, so a result does
+//    not depend on scheduling.  The split count is a function of (N, K) up to 128 rows; above, it
+//    also depends on the number of row tiles (gemm_plan), so a row's low-order bits can differ
+//    between a block of 320 rows and a block of 68.
 //
 // fp32 path (tiny configuration): plain LDS-tiled FMA kernel with bounds checks, row-major weights.
 #include <algorithm>
@@ -91,43 +95,82 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
     constexpr int A_STAGE = MT * 4096, STAGE = A_STAGE + 4 * NB * 4096;
     constexpr int LOADS = MT + 4 * NB;                    // per wave and chunk
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const bool loader = wave_u >= 4;                      // waves 4..7 only move data, for waves 0..3
+    const int lw = wave_u & 3;
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     auto swz = [](int r) { return (r & 7) ^ ((r >> 3) & 1); };
-    const bf16_t* apr[MT];
+    // Every load is "wave-uniform base in scalar registers + per-lane byte offset + constant": the
+    // chunk index only moves the scalar base, so issuing a load costs no vector instruction besides
+    // the load itself (address arithmetic in the vector unit would take issue slots from the MFMAs).
+    uint32_t aoff[MT];                                    // byte offset of this lane's piece within a chunk's rows
 #pragma unroll
     for (int j = 0; j < MT; ++j) {
-      const int pr = wave_u + 4 * j;                      // row tile pr / 4, rows 8 (pr % 4) .. + 7 of it
+      const int pr = lw + 4 * j;                          // row tile pr / 4, rows 8 (pr % 4) .. + 7 of it
       const int rt = 8 * (pr & 3) + (lane >> 3);
       int m = min(mt0 + (pr >> 2) * 32 + rt, M - 1);
       if (a_rows) m = max(a_rows[m], 0);
-      apr[j] = A + (a_ld > 0 ? (size_t)m * KC : (size_t)m * K) + 8 * ((lane & 7) ^ swz(rt));
+      aoff[j] = (uint32_t)(((a_ld > 0 ? (size_t)m * KC : (size_t)m * K) + 8 * ((lane & 7) ^ swz(rt))) * 2);
     }
     int a_rd[4];                                          // this lane's fragment of step s inside a row tile
 #pragma unroll
     for (int st = 0; st < 4; ++st) a_rd[st] = lr * 128 + (((4 * lg + st) ^ swz(lr)) << 4);
-    const size_t a_cs = a_ld > 0 ? (size_t)a_ld * KC : (size_t)KC;
-    const u32x4_t* wpr[NB];
+    const size_t a_cs = (a_ld > 0 ? (size_t)a_ld * KC : (size_t)KC) * 2;          // bytes between chunks
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(A);
+    const int n0u = ni * (128 * NB) + lw * (32 * NB);     // n0 of the wave served, known to be wave-uniform
+    const unsigned char* w_base[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int blk = min((n0 + nb * 32) >> 5, (N >> 5) - 1);   // clamped: computed, never stored
-      wpr[nb] = reinterpret_cast<const u32x4_t*>(W) + (size_t)blk * 256 + lane;
+      const int blk = min((n0u + nb * 32) >> 5, (N >> 5) - 1);   // clamped: computed, never stored
+      w_base[nb] = reinterpret_cast<const unsigned char*>(W) + (size_t)blk * 4096;
     }
-    const size_t W_CHUNK = (size_t)(N >> 5) * 256;
+    const size_t W_CHUNK = (size_t)(N >> 5) * 4096;       // bytes between chunks of the packed weights
+    const uint32_t lane16 = (uint32_t)lane * 16;
     // load l of a chunk: l < MT activation quarter-tiles, then the weights (column block, step)
     auto issue_one = [&](int l, int c, uint32_t sb) {
       if (l < MT) {
-        load_to_lds16(apr[l] + (size_t)c * a_cs, sb + (wave_u + 4 * l) * 1024);
+        load_to_lds16_sbase<0>(a_base + (size_t)c * a_cs, aoff[l], sb + (lw + 4 * l) * 1024);
       } else {
         const int nb = (l - MT) >> 2, st = (l - MT) & 3;
-        load_to_lds16(wpr[nb] + (size_t)c * W_CHUNK + st * 64, sb + A_STAGE + (wave_u * NB + nb) * 4096 + st * 1024);
+        const unsigned char* src = w_base[nb] + (size_t)c * W_CHUNK;
+        const uint32_t dst = sb + A_STAGE + (lw * NB + nb) * 4096;
+        // the constant is added to the global and to the LDS address alike
+        if (st == 0) load_to_lds16_sbase<0>(src, lane16, dst);
+        else if (st == 1) load_to_lds16_sbase<1024>(src, lane16, dst);
+        else if (st == 2) load_to_lds16_sbase<2048>(src, lane16, dst);
+        else load_to_lds16_sbase<3072>(src, lane16, dst);
       }
     };
-    // One chunk of matrix work from `stage`; with `pre` the loads of chunk c_pre go out between
-    // the MFMA groups, spread evenly.  (Issued as one burst they would hold the wave at the
-    // memory pipeline's address queue -- the four waves' loads take about as long to drain as
-    // the chunk's MFMAs take to run -- and the matrix cores would idle meanwhile.)
-    auto chunk = [&](int stage, bool pre, int c_pre, int stage_pre) {
-      const uint32_t sb = lds0 + stage_pre * STAGE;
+    // The loads are issued by four waves of their own.  (Issued by the computing waves between their
+    // MFMAs, every load costs the wave a dozen scalar instructions for base, LDS address and M0, and
+    // a wave issues in order: the matrix core idles meanwhile.  A second wave per SIMD issues them
+    // in the shadow of the first one's MFMAs.)  Loading wave 4 + w brings in the activation
+    // quarter-tiles w, w + 4, ... and the weights of computing wave w; chunk c + 2 goes out once
+    // every wave has passed the barrier of chunk c, i.e. is done with chunk c - 1, whose stage it takes.
+    const int nc = c_end - c_begin;
+    if (loader) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        if (u < nc)
+#pragma unroll
+          for (int l = 0; l < LOADS; ++l) issue_one(l, c_begin + u, lds0 + u * STAGE);
+      int stage = 2;
+      for (int c = 0; c < nc; ++c) {
+        // chunk c has landed (this wave's part; the barrier covers the other waves'), chunk c + 1
+        // stays in flight
+        if (c + 1 < nc) wait_loads_but<LOADS>();
+        else wait_loads_but<0>();
+        __syncthreads();
+        if (c + 2 < nc) {
+#pragma unroll
+          for (int l = 0; l < LOADS; ++l) issue_one(l, c_begin + c + 2, lds0 + stage * STAGE);
+        }
+        stage = stage + 1 == RING ? 0 : stage + 1;
+      }
+      __syncthreads();
+      return;
+    }
+    // One chunk of matrix work from `stage`
+    auto chunk = [&](int stage) {
       const unsigned char* sa = lds + stage * STAGE;
       const unsigned char* sw = sa + A_STAGE + wave_u * NB * 4096 + lane * 16;
       bf16x8_t af[2][MT], wf[2][NB];
@@ -143,11 +186,6 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
             af[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(sa + i * 4096 + a_rd[st + 1]);
             if (i < NB) wf[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(sw + i * 4096 + (st + 1) * 1024);
           }
-          {   // LOADS loads spread evenly over the 4 MT groups
-            constexpr int SLOTS = 4 * MT;
-            const int q = st * MT + i;
-            if ((q * LOADS) / SLOTS != ((q + 1) * LOADS) / SLOTS && pre) issue_one((q * LOADS) / SLOTS, c_pre, sb);
-          }
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
@@ -156,21 +194,10 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
         }
       }
     };
-    static_assert(LOADS <= 4 * MT, "one load per MFMA group");
-    const int nc = c_end - c_begin;
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-      if (u < nc)
-#pragma unroll
-        for (int l = 0; l < LOADS; ++l) issue_one(l, c_begin + u, lds0 + u * STAGE);
     int stage = 0;
     for (int c = 0; c < nc; ++c) {
-      // chunk c has landed (this wave's part; the barrier covers the other waves'), chunk c + 1
-      // stays in flight
-      if (c + 1 < nc) wait_loads_but<LOADS>();
-      else wait_loads_but<0>();
-      __syncthreads();                                    // also: everyone is done with chunk c - 1's stage
-      chunk(stage, c + 2 < nc, c_begin + c + 2, stage >= RING - 2 ? stage + 2 - RING : stage + 2);
+      __syncthreads();                                    // chunk c has landed; everyone is done with chunk c - 1
+      chunk(stage);
       stage = stage + 1 == RING ? 0 : stage + 1;
     }
     __syncthreads();                                      // the epilogues reuse the LDS
@@ -422,13 +449,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                                            nullptr, 0u);
 }
 
-// Large tile with the LDS ring: one workgroup per CU owns (almost) the whole LDS.
+// Large tile with the LDS ring: one workgroup of eight waves per CU owns (almost) the whole LDS;
+// waves 0..3 compute, waves 4..7 load (two waves per SIMD, 256 registers each: the 160 accumulator
+// registers of a 5 x 2 tile fit).
 constexpr int RING_STAGES = 3;
 template <int MT, int NB>
 constexpr size_t ring_lds_bytes() { return (size_t)RING_STAGES * (MT * 4096 + 4 * NB * 4096); }
 
 template <int MT, int NB, int EPI>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_ring(
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bf16_ring(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
     float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
     float* __restrict__ out2) {
@@ -522,7 +551,7 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
     const hipError_t attr = ring_allow_lds<MT, NB, EPI>();
     if (attr != hipSuccess) return attr;
     const size_t ring_bytes = ring_lds_bytes<MT, NB>();
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), ring_bytes, st, (const bf16_t*)A, a_rows,
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), ring_bytes, st, (const bf16_t*)A, a_rows,
                        (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2);
   } else if constexpr (MT * NB >= 8)
     hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st,
