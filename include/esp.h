@@ -298,6 +298,15 @@ size_t esp_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 esp_status esp_gemm(void *stream, int32_t dtype, const void *A, const void *W, int32_t w_packed,
                     float *C, int32_t M, int32_t N, int32_t K, void *partials, size_t partial_bytes);
 
+/* LM head with the greedy choice of Sec. 2 Eq. 3 taken in the GEMM's epilogue (the path
+ * esp_tree_forward uses at the tree rows): argmax[m] = arg-max over n of A[m,:] . W[n,:], lowest n on
+ * ties, for bf16 A[M,K] and W[N,K] in the streaming layout (both device).  The [M,N] logits are never
+ * written.  `scratch`: device, esp_gemm_argmax_scratch_bytes(M,N) bytes (per-tile (value, index)
+ * pairs).  ESP_ESHAPE if N % 32 or K % 64. */
+size_t esp_gemm_argmax_scratch_bytes(int32_t M, int32_t N);
+esp_status esp_gemm_argmax(void *stream, const void *A, const void *W, int32_t M, int32_t N, int32_t K,
+                           void *scratch, size_t scratch_bytes, int32_t *argmax);
+
 /* Tree-masked grouped-query attention of one layer (the kernel esp_tree_forward uses):
  * q device [batch*rows_per_seq, n_q_heads, head_dim] model dtype, already rotated; K/V of the
  * block rows already in the cache at len[b]+row; out same shape as q. */

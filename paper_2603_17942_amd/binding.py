@@ -59,7 +59,7 @@ class TreeParams(C.Structure):
 EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy", "esp_last_device_status",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
            "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_mask_last_k", "esp_mask_gaussian", "esp_kv_store", "esp_kv_load",
-           "esp_gemm_scratch_bytes", "esp_gemm", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
+           "esp_gemm_scratch_bytes", "esp_gemm", "esp_gemm_argmax_scratch_bytes", "esp_gemm_argmax", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
            "esp_softmax_topk", "esp_softmax_topk_static", "esp_profile_enable", "esp_profile_read", "esp_pack_weight", "esp_set_sampling"]
 SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
 
@@ -103,6 +103,9 @@ def load_library() -> C.CDLL:
     lib.esp_gemm_scratch_bytes.restype = C.c_size_t
     lib.esp_gemm_scratch_bytes.argtypes = [_i32, _i32, _i32]
     lib.esp_gemm.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _vp, C.c_size_t]
+    lib.esp_gemm_argmax_scratch_bytes.restype = C.c_size_t
+    lib.esp_gemm_argmax_scratch_bytes.argtypes = [_i32, _i32]
+    lib.esp_gemm_argmax.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, C.c_size_t, _vp]
     lib.esp_pack_weight.argtypes = [_vp, _vp, _vp, _i32, _i32]
     lib.esp_attn_tree.argtypes = [_vp, P(Block), P(Kv), _i32, _vp, _vp]
     lib.esp_softmax_topk_scratch_bytes.restype = C.c_size_t
@@ -431,6 +434,25 @@ def gemm(A: torch.Tensor, W: torch.Tensor, packed: bool = False, out: Optional[t
     assert scratch.numel() >= nb and out.shape == (M, N) and out.dtype == torch.float32
     _check(lib.esp_gemm(_stream_ptr(), code, _ptr(A), _ptr(W), int(packed), _ptr(out), M, N, K, _ptr(scratch),
                         nb), "esp_gemm")
+    return out
+
+
+def gemm_argmax(A: torch.Tensor, W_packed: torch.Tensor, out: Optional[torch.Tensor] = None,
+                scratch: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[M] int32 = arg-max over n of A[M,K] @ W[N,K]^T (bf16, W packed), lowest n on ties, through
+    esp_gemm_argmax: the logits are never written."""
+    lib = load_library()
+    M, K = A.shape
+    N = W_packed.shape[0]
+    assert A.dtype == torch.bfloat16 and W_packed.dtype == torch.bfloat16
+    if out is None:
+        out = torch.empty(M, dtype=torch.int32, device=A.device)
+    nb = lib.esp_gemm_argmax_scratch_bytes(M, N)
+    if scratch is None:
+        scratch = torch.empty(max(nb, 256), dtype=torch.uint8, device=A.device)
+    assert scratch.numel() >= nb and out.numel() >= M and out.dtype == torch.int32
+    _check(lib.esp_gemm_argmax(_stream_ptr(), _ptr(A), _ptr(W_packed), M, N, K, _ptr(scratch), nb, _ptr(out)),
+           "esp_gemm_argmax")
     return out
 
 

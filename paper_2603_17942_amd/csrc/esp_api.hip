@@ -394,7 +394,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_node_rows(s, bd, nb, c->idx_a, c->idx_b, kd.len, c->idx_d));
       if (c->sample_on) ESP_HIP(launch_row_positions(s, bd, kd.len, c->idx_c)); }
-    if (blk->k_masks > 0 && gemm_argmax_supported(dt, M, m.vocab, d) && (size_t)M <= c->logits_rows &&
+    if (blk->k_masks > 0 && gemm_argmax_supported(dt, M, m.vocab, d, true) && (size_t)M <= c->logits_rows &&
         gemm_argmax_scratch_floats(M, m.vocab) <= c->gemm_out_floats) {
       // few rows (<= 128): one pass over the LM head for all block rows.  The tree rows get their
       // arg-max from the epilogue; the logits of every row stay in the workspace, where
@@ -406,7 +406,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
                                  c->sample_seed));
       c->lm_cache_hidden = hidden_out;
       c->lm_cache_rows = M;
-    } else if (gemm_argmax_supported(dt, Mn, m.vocab, d) &&
+    } else if (gemm_argmax_supported(dt, Mn, m.vocab, d, false) &&
         gemm_argmax_scratch_floats(Mn, m.vocab) <= c->logits_rows * (size_t)m.vocab) {
       // arg-max in the GEMM epilogue: the [rows, vocab] logits are never written
       ESP_PROF(ESP_SITE_LM_HEAD);
@@ -612,6 +612,22 @@ esp_status esp_gemm(void* stream, int32_t dtype, const void* A, const void* W, i
   hipLaunchKernelGGL(k_reduce_splits, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)partials,
                      p.splits, n, C);
   ESP_HIP(hipGetLastError());
+  return ESP_OK;
+}
+
+size_t esp_gemm_argmax_scratch_bytes(int32_t M, int32_t N) {
+  if (M < 1 || N < 1) return 0;
+  return gemm_argmax_scratch_floats(M, N) * 4;
+}
+
+esp_status esp_gemm_argmax(void* stream, const void* A, const void* W, int32_t M, int32_t N, int32_t K, void* scratch,
+                           size_t scratch_bytes, int32_t* argmax) {
+  if (!A || !W || !argmax || M < 1 || N < 1 || K < 1) return ESP_EINVAL;
+  if (N % 32 || K % 64) return ESP_ESHAPE;
+  if (!gemm_argmax_supported(ESP_BF16, M, N, K, false)) return ESP_ESHAPE;
+  if (!scratch || scratch_bytes < gemm_argmax_scratch_floats(M, N) * 4) return ESP_ECAPACITY;
+  ESP_HIP(launch_gemm_argmax((hipStream_t)stream, A, nullptr, W, M, N, K, (float*)scratch, argmax, nullptr, 0, nullptr,
+                             nullptr, M, nullptr, 0u));
   return ESP_OK;
 }
 

@@ -460,10 +460,10 @@ template <int MT, int NB, int EPI>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bf16_ring(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ a_rows, const bf16_t* __restrict__ W,
     float* __restrict__ out, int M, int N, int K, int splits, int m_tiles, int n_tiles, int a_ld,
-    float* __restrict__ out2) {
+    float* __restrict__ out2, const int32_t* __restrict__ draw_pos, uint32_t seed) {
   extern __shared__ __align__(16) unsigned char lds[];
   gemm_bf16_body<MT, NB, 2, true, 1, EPI, RING_STAGES>(lds, A, a_rows, W, out, M, N, K, splits, m_tiles, n_tiles, a_ld,
-                                                      out2, nullptr, 0u);
+                                                      out2, draw_pos, seed);
 }
 
 // ---- fp32: 64x64 tile, 16-deep k steps, 256 threads, 4x4 outputs per thread -----------------------
@@ -552,7 +552,7 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
     if (attr != hipSuccess) return attr;
     const size_t ring_bytes = ring_lds_bytes<MT, NB>();
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), ring_bytes, st, (const bf16_t*)A, a_rows,
-                       (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2);
+                       (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2, draw_pos, seed);
   } else if constexpr (MT * NB >= 8)
     hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st,
                        (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles,
@@ -570,6 +570,8 @@ hipError_t gemm_prepare() {
   if (e == hipSuccess) e = ring_allow_lds<4, 2, 2>();
   if (e == hipSuccess) e = ring_allow_lds<5, 2, 0>();
   if (e == hipSuccess) e = ring_allow_lds<5, 2, 2>();
+  if (e == hipSuccess) e = ring_allow_lds<4, 2, 1>();
+  if (e == hipSuccess) e = ring_allow_lds<5, 2, 1>();
   return e;
 }
 
@@ -636,12 +638,16 @@ __global__ __launch_bounds__(256) void k_argmax_tiles(const float* __restrict__ 
 
 }  // namespace
 
-// LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows):
-// scratch holds n_tiles * M (value, column) pairs; out[out_index[m]] = arg-max of row m.
-bool gemm_argmax_supported(int dtype, int M, int N, int K) {
+// LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights): scratch holds
+// n_tiles * M (value, column) pairs; out[out_index[m]] = arg-max of row m.  Up to 128 rows the
+// logits of all rows can be written as well (logits_out); above, the large-tile kernel takes the
+// arg-max only and the [rows, vocab] logits are never written.
+bool gemm_argmax_supported(int dtype, int M, int N, int K, bool with_logits) {
   if (dtype != ESP_BF16) return false;
   GemmPlan p = gemm_plan(dtype, M, N, K);
-  return p.nb == 1 && p.splits == 1 && p.m_tiles == 1;
+  if (p.splits != 1) return false;
+  if (p.nb == 1 && p.m_tiles == 1) return true;
+  return !with_logits && p.nb == 2 && p.mt >= 3 && p.mt <= 5;
 }
 size_t gemm_argmax_scratch_floats(int M, int N) { return (size_t)((N + 127) / 128) * M * 2; }
 
@@ -660,11 +666,18 @@ hipError_t launch_gemm_argmax(hipStream_t st, const void* A, const int32_t* a_ro
                    : launch_bf16<MT_, 1, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld, nullptr,     \
                                                      draw_pos, seed);                                          \
     break;
-  switch (p.mt) {
-    ESP_AMAX_CASE(1)
-    ESP_AMAX_CASE(2)
-    ESP_AMAX_CASE(3)
-    ESP_AMAX_CASE(4)
+  if (p.nb == 2) {   // many rows: large tiles, pairs only
+    if (logits_out) return hipErrorInvalidValue;
+    if (p.mt == 3) e = launch_bf16<3, 2, true, 4, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld, nullptr, draw_pos, seed);
+    else if (p.mt == 4) e = launch_bf16<4, 2, true, 2, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld, nullptr, draw_pos, seed);
+    else if (p.mt == 5) e = launch_bf16<5, 2, true, 2, 1>(st, A, a_rows, W, scratch, M, N, K, p, a_ld, nullptr, draw_pos, seed);
+  } else {
+    switch (p.mt) {
+      ESP_AMAX_CASE(1)
+      ESP_AMAX_CASE(2)
+      ESP_AMAX_CASE(3)
+      ESP_AMAX_CASE(4)
+    }
   }
 #undef ESP_AMAX_CASE
   if (e != hipSuccess) return e;

@@ -120,7 +120,7 @@ hipError_t launch_pack_weight(hipStream_t st, const void* src, void* dst, int N,
 hipError_t gemm_prepare();
 hipError_t launch_gemm_swiglu(hipStream_t st, const void* A, const void* W, void* act, int M, int ff, int K);
 // LM head with the arg-max taken in the GEMM epilogue (bf16, packed weights, <= 128 rows, one split)
-bool gemm_argmax_supported(int dtype, int M, int N, int K);
+bool gemm_argmax_supported(int dtype, int M, int N, int K, bool with_logits);
 size_t gemm_argmax_scratch_floats(int M, int N);
 // logits_out == NULL: arg-max of each of the M rows (out[out_index[m]]), logits never written.
 // logits_out != NULL: also writes the fp32 logits [M][N]; arg-max only for the n_arg rows arg_rows[i].

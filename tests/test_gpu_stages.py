@@ -48,6 +48,32 @@ def test_gemm_bf16(B, M, N, K):
         assert np.array_equal(got1[0], got[0])
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 512, 128), (68, 4096, 256), (128, 1056, 192), (129, 768, 256), (320, 4096, 512),
+                                   (200, 2048, 128), (1344, 1280, 256), (700, 33 * 32, 192), (180, 512, 64)])
+def test_gemm_argmax_epilogue(B, M, N, K):
+    """Sec. 2 Eq. 3: the greedy choice per row, taken in the LM-head GEMM's epilogue (small-tile kernel up
+    to 128 rows, large-tile kernel above).  Against the same GEMM's written logits the arg-max must be
+    exact, lowest index on ties; planted exact ties (duplicated weight rows) make the tie rule visible,
+    also across column tiles and across the waves of a workgroup."""
+    print(f"gemm arg-max M={M} N={N} K={K}", flush=True)
+    a = synth.normal_like((M, K), 1.0, 13, 0, "cuda", torch.bfloat16)
+    w = synth.normal_like((N, K), 0.05, 13, 1, "cuda", torch.bfloat16)
+    # duplicate the winning weight row of a few rows at a higher and a lower index
+    logits0 = B.gemm(a, w)
+    win = logits0.argmax(dim=1)
+    for r in range(0, M, max(1, M // 7)):
+        n = int(win[r])
+        for other in ((n + 40) % N, (n + N - 300) % N, (n + 129) % N):
+            w[other] = w[n]
+    wp = B.pack_weight(w)
+    logits = B.gemm(a, wp, packed=True).cpu().numpy()
+    want = np.array([O.argmax_lowest(row) for row in logits], dtype=np.int32)
+    got = B.gemm_argmax(a, wp).cpu().numpy()
+    assert np.array_equal(got, want), np.nonzero(got != want)[0][:8]
+    ties = int(sum((logits[i] == logits[i].max()).sum() > 1 for i in range(M)))
+    assert ties >= 1
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (13, 4096, 256), (52, 688, 256), (52, 256, 688), (70, 130, 77)])
 def test_gemm_f32(B, M, N, K):
     print(f"gemm f32 M={M} N={N} K={K}", flush=True)
