@@ -8,8 +8,13 @@ Workload: Llama-3-8B-shaped random bf16 decoder, KV cache of a 2048-token random
 on the GPU), 4 mask tokens, Top-K 8, tree of 64 nodes, batch 1.  All inputs are synthetic and
 resident in HBM before the timed region.
 
-Prints ONE JSON line (see the design doc for the fields).  --gpus above 1 is refused: this build is
-single-GPU by construction.
+Besides that workload the line carries: the other layout, HIP-graph replay, the one-row
+autoregressive baseline, a block-complexity sweep, steps with planted acceptance (mean 1.7 tokens per
+step), stage figures (attention at a 32768-token cache, LM head at 1344 rows, softmax + Top-K'), the
+other workloads as whole steps (32768-token cache; batch 16 with ragged lengths; Qwen3-8B shape) and
+the CPU oracle's rate.
+
+Prints ONE JSON line.  --gpus above 1 is refused: this build is single-GPU by construction.
 """
 import argparse
 import json
@@ -33,6 +38,20 @@ def layer_gemm_shapes(s):
 def gemm_algorithmic_bytes(M, N, K):
     """Weights once + activations in (bf16) + one fp32 result out."""
     return 2 * N * K + 2 * M * K + 4 * M * N
+
+
+def layer_algorithmic_bytes(s, M):
+    """Bytes the four projections of a layer must move for M rows: every weight once, the bf16
+    activations in, and what each result is handed on as (fp32 for QKV, O and down, whose consumers
+    add the residual or rotate in fp32; bf16 [M, d_ff] for the gate/up projection, whose SwiGLU runs
+    in the epilogue)."""
+    (nq, d), (_, ko), (n_gu, _), (_, ff) = layer_gemm_shapes(s)
+    return (2 * nq * d + 2 * M * d + 4 * M * nq) + (2 * d * ko + 2 * M * ko + 4 * M * d) + \
+        (2 * n_gu * d + 2 * M * d + 2 * M * ff) + (2 * d * ff + 2 * M * ff + 4 * M * d)
+
+
+HBM_SUSTAINED_GBS = 6200.0      # plain streaming kernel on this GPU (measured), for context
+MFMA_SUSTAINED_TFLOPS = 1880.0  # back-to-back MFMA loop on this GPU (measured; the clock drops under matrix load)
 
 
 PMC_SUMMARY = os.path.join(ROOT, "profiles", "esp_step_llama3_8b_kv2048_hbm_traffic_pmc.txt")
@@ -67,7 +86,7 @@ def run_config(B, decode, synth, torch, shape, weights, eng_holder, layout, n_no
     eng = dec.eng
     torch.cuda.synchronize()
     tp0 = time.perf_counter()
-    dec.prefill([prompt])                        # chunks of 256 rows through esp_tree_forward (Sec. 3.3)
+    dec.prefill([prompt])                        # chain blocks of PREFILL_CHUNK rows through esp_tree_forward (Sec. 3.3)
     torch.cuda.synchronize()
     prefill_ms = (time.perf_counter() - tp0) * 1e3
     dec.step()                                   # root-only step: seeds the first 64-node tree
@@ -112,6 +131,180 @@ def run_config(B, decode, synth, torch, shape, weights, eng_holder, layout, n_no
     return dict(dec=dec, ms_per_step=(t1 - t0) * 1e3 / steps, emitted=emitted, prefill_ms=prefill_ms,
                 step_ms_p10_p50_p90=[round(pct(0.1), 4), round(pct(0.5), 4), round(pct(0.9), 4)], n_spans=n_spans, span_ms=span_ms,
                 breakdown=breakdown, n_nodes=n_nodes_now, rows=rows_now, len_end=int(dec.kv.len[0]))
+
+
+def run_case(B, decode, synth, torch, shape, weights, eng_holder, layout, n_nodes, k, K, kp, lens, steps, warmup,
+             node_counts=None, ema=0.0):
+    """A step workload with the KV cache filled directly (seeded N(0,1) bf16, the same values in every
+    layer: a prompt of tens of thousands of tokens is not prefilled here).  lens: cache length per
+    sequence.  node_counts: None = rolling steps (every step verifies the tree the step before built,
+    which fills the node budget); a list = every timed step starts from the same seeded random trees
+    with that many nodes per sequence (block arrays and cache lengths are put back by device-side
+    copies inside the timed region: a few microseconds)."""
+    batch = len(lens)
+    params = B.tree_params(n_nodes, k, K, 0, True, False, layout)
+    caps = [l + (steps + warmup + 24) * (k + 1) + 1024 for l in lens]
+    dec = decode.EspDecoder(shape, weights, params, kp, caps, prefill_chunk=64, ema_lambda=ema,
+                            engine=eng_holder.get("eng"))
+    eng_holder["eng"] = dec.eng
+    eng = dec.eng
+    one = shape.replace(n_layers=1)
+    kf, vf = synth.make_kv_fill(one, max(lens), seed=5, device="cuda")
+    for b in range(batch):
+        kb, vb = kf[0][:lens[b]].contiguous(), vf[0][:lens[b]].contiguous()
+        for l in range(shape.n_layers):
+            eng.kv_store(dec.kv, l, b, 0, kb, vb)
+    del kf, vf
+    dec.kv.set_len(lens)
+    eng.mask_mean(synth.make_prompt(256, shape.vocab, seed=2).to("cuda", torch.int32), k, dec.mask_embed)
+    counts = node_counts if node_counts is not None else [n_nodes] * batch
+    trees = [synth.make_random_tree(counts[b], k, shape.vocab, seed=7 + b) for b in range(batch)]
+    dec.set_tree([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])
+    fixed = node_counts is not None
+    if fixed:
+        names = [n for n, t in vars(dec.cur).items() if torch.is_tensor(t)]
+        saved = {n: getattr(dec.cur, n).clone() for n in names}
+        len0 = dec.kv.len.clone()
+        bound0 = dec.kv.len_bound
+
+        def restore():
+            for n in names:
+                getattr(dec.cur, n).copy_(saved[n])
+            dec.kv.len.copy_(len0)
+            dec.kv.len_bound = bound0
+    else:
+        def restore():
+            pass
+    for _ in range(warmup):
+        restore()
+        dec.step()
+    torch.cuda.synchronize()
+    rows_now = int(dec.cur.n_rows.sum()) if not fixed else int(saved["n_rows"].sum())
+    nodes_now = int(dec.cur.n_nodes.sum()) if not fixed else int(saved["n_nodes"].sum())
+    eng.profile_read("gemm_layer")
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    lsum0 = int(dec.kv.len.sum())
+    emitted = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        restore()
+        dec.step()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    emitted = (int(dec.kv.len.sum()) - lsum0) if not fixed else steps * (int(dec.kv.len.sum()) - int(len0.sum()))
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    sites = list(B.SITES)
+    for st in sites:
+        eng.profile_read(st)
+    eng.profile_enable(sites)
+    nb = 2
+    for _ in range(nb):
+        restore()
+        dec.step()
+    eng.profile_enable([])
+    breakdown = {}
+    for st in sites:
+        n, ms = eng.profile_read(st)
+        breakdown[st] = {"launches_per_step": n / nb, "ms_per_step": ms / nb}
+    status = eng.device_status()
+    assert status == 0, f"device status {status}"
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    M = batch * dec.rows_per_seq                       # rows every launch is sized for
+    g = breakdown["gemm_layer"]
+    g_ms = g["ms_per_step"] / max(g["launches_per_step"], 1)
+    lay_bytes = layer_algorithmic_bytes(shape, rows_now) / 4
+    lay_flops = sum(2.0 * rows_now * N * Kd for N, Kd in layer_gemm_shapes(shape)) / 4
+    a = breakdown["attn"]
+    a_ms = (a["ms_per_step"] + breakdown["attn_merge"]["ms_per_step"]) / max(a["launches_per_step"], 1)
+    kv_rows = int(sum(lens)) + rows_now
+    attn_bytes = kv_rows * shape.n_kv_heads * shape.head_dim * 2 * 2 + 2 * rows_now * shape.n_q_heads * shape.head_dim * 2
+    attn_flops = sum(4.0 * (dec.rows_per_seq if not fixed else int(saved["n_rows"][b])) * shape.n_q_heads * shape.head_dim *
+                     (lens[b] + dec.rows_per_seq) for b in range(batch))
+    res = {"layout": "per_node" if layout == B.LAYOUT_PER_NODE else "root_chain", "batch": batch,
+           "rows_per_step": rows_now, "rows_launched": M, "tree_nodes": nodes_now, "kv_len": lens if batch <= 2 else
+           {"min": min(lens), "max": max(lens), "sum": int(sum(lens))},
+           "ms_per_step": ms_per_step, "step_ms_p10_p50_p90": [round(pct(0.1), 4), round(pct(0.5), 4), round(pct(0.9), 4)],
+           "tokens_per_s": emitted / (ms_per_step * steps / 1e3), "tau_measured": emitted / (steps * batch),
+           "steps": steps, "trees": "fixed seeded random trees" if fixed else "rolling (built by the step before)",
+           "breakdown_ms_per_step": {st: round(v["ms_per_step"], 4) for st, v in breakdown.items()},
+           "roofline": {"kernel": "layer projections (QKV, O, gate/up, down), mean of the four launches",
+                        "bound": "hbm" if rows_now < 300 else "mfma",
+                        "bytes_per_launch": lay_bytes, "flops_per_launch": lay_flops, "avg_launch_ms": g_ms,
+                        "hbm_gbs": lay_bytes / (g_ms * 1e-3) / 1e9, "hbm_frac": lay_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "mfma_tflops": lay_flops / (g_ms * 1e-3) / 1e12,
+                        "mfma_frac": lay_flops / (g_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+           "roofline_attn": {"kernel": "k_attn_ring + k_attn_merge_ring, per layer", "bound": "hbm",
+                             "bytes_per_launch": attn_bytes, "avg_launch_ms": a_ms,
+                             "achieved": attn_bytes / (a_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": attn_bytes / (a_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "mfma_tflops": attn_flops / (a_ms * 1e-3) / 1e12}}
+    del dec
+    return res
+
+
+PLANTED_DEPTHS = [0] * 20 + [1] * 12 + [2] * 8   # accepted nodes per step: mean 0.70
+
+
+def planted_acceptance(B, torch, dec, seed=11):
+    """Steps with planted acceptance: random weights accept nothing, so before each timed step the
+    tree the method built is edited on the device -- along one path from the root, down to a planted
+    depth, a child's token is replaced by the token the base model itself produces at its parent
+    (found by running the forward on the same block, untimed).  The timed step then verifies and
+    commits that path like any other.  The planted depths are a shuffled multiset (20 steps accept
+    nothing, 12 one node, 8 two nodes) whose mean, 1.70 tokens per step with the bonus token, lies in
+    the range the paper reports for trained 8B models (Table 1: 1.63 to 1.74).  Depth stops at two:
+    with random weights the Top-K' probabilities are nearly flat, so the pruned 64-node tree the method
+    builds is the root, its 8 children and 55 grandchildren."""
+    import random
+    depths = list(PLANTED_DEPTHS)
+    random.Random(seed).shuffle(depths)
+    steps = len(depths)
+    eng, k = dec.eng, dec.k
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    lens = []
+    for i in range(steps):
+        n = int(dec.cur.n_nodes[0])
+        tok = dec.cur.tok[:n].tolist()
+        par = dec.cur.parent[:n].tolist()
+        children = [[] for _ in range(n)]
+        for c in range(1, n):
+            children[par[c]].append(c)
+        height = [0] * n                          # parents precede children: one backward sweep
+        for c in range(n - 1, 0, -1):
+            height[par[c]] = max(height[par[c]], height[c] + 1)
+        node = 0
+        for d in range(min(depths[i], k)):
+            if not children[node]:
+                break
+            eng.tree_forward(dec.cur, dec.mask_embed, dec.kv, dec.hidden, dec.node_argmax, None)
+            g = int(dec.node_argmax[node])
+            hit = [c for c in children[node] if tok[c] == g]
+            # no child carries the token already: overwrite the child with the deepest subtree below it
+            c = hit[0] if hit else max(children[node], key=lambda x: height[x])
+            dec.cur.tok[c] = g
+            tok[c] = g
+            node = c
+        torch.cuda.synchronize()
+        l0 = int(dec.kv.len[0])
+        e0[i].record()
+        dec.step()
+        e1[i].record()
+        torch.cuda.synchronize()
+        lens.append(int(dec.kv.len[0]) - l0)
+        dec.kv.len_bound = int(dec.kv.len[0])
+    ms = sum(a.elapsed_time(b) for a, b in zip(e0, e1))
+    assert eng.device_status() == 0
+    hist = {str(n): lens.count(n) for n in sorted(set(lens))}
+    return {"tokens_per_s": sum(lens) / (ms * 1e-3), "tau_measured": sum(lens) / steps, "ms_per_step": ms / steps,
+            "steps": steps, "planted_tokens_per_step": 1.0 + sum(min(d, k) for d in depths) / steps,
+            "tokens_per_step_histogram": hist,
+            "note": "acceptance planted on the device before each timed step (see the docstring of "
+                    "planted_acceptance); tau is what the verifier then measured, not the paper's"}
 
 
 def ar_baseline(B, torch, dec, steps):
@@ -219,9 +412,10 @@ def stage_rooflines(B, synth, torch, shape, lm_head_packed):
         byts = (L + rows) * sh.n_kv_heads * sh.head_dim * 2 * 2 + 2 * rows * sh.n_q_heads * sh.head_dim * 2
         flops = 4.0 * rows * sh.n_q_heads * sh.head_dim * (L + rows)
         out[f"attn_L32768_rows{rows}"] = {
-            "kernel": "k_attn_mfma + k_attn_merge", "bound": "hbm", "achieved": byts / ms / 1e6, "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": byts / ms / 1e6 / HBM_PEAK_GBS, "bytes_per_launch": byts, "avg_launch_ms": ms,
-            "mfma_tflops": flops / ms / 1e9}
+            "kernel": "k_attn_ring + k_attn_merge_ring", "bound": "hbm", "achieved": byts / ms / 1e6, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": byts / ms / 1e6 / HBM_PEAK_GBS,
+            "frac_of_sustained_6200": byts / ms / 1e6 / HBM_SUSTAINED_GBS, "bytes_per_launch": byts, "avg_launch_ms": ms,
+            "mfma_tflops": flops / ms / 1e9, "mfma_frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
     assert eng.device_status() == 0
     eng.close()
     del eng, kv, kf, vf, w
@@ -279,6 +473,9 @@ def main():
     ap.add_argument("--no-stages", action="store_true", help="skip the stage-level roofline figures")
     ap.add_argument("--no-sweep", action="store_true", help="skip the block-complexity sweep")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--no-planted", action="store_true", help="skip the planted-acceptance run")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the other workloads (long context, batch 16, Qwen3 shape)")
     ap.add_argument("--fast-weights", action="store_true",
                     help="draw the weights with torch.Tensor.normal_ (one kernel per tensor) instead of the "
                          "counter-based generator; for counter-collection runs, where tens of thousands of "
@@ -339,7 +536,8 @@ def main():
         rows = r["rows"]
         tokens_per_s = r["emitted"] / (r["ms_per_step"] * args.steps / 1e3)
         shapes = layer_gemm_shapes(shape)
-        per_launch = sum(gemm_algorithmic_bytes(rows, N, Kd) for N, Kd in shapes) / len(shapes)
+        per_launch_fp32 = sum(gemm_algorithmic_bytes(rows, N, Kd) for N, Kd in shapes) / len(shapes)
+        per_launch = layer_algorithmic_bytes(shape, rows) / len(shapes)
         avg_ms = r["span_ms"] / max(r["n_spans"], 1)
         achieved = per_launch / (avg_ms * 1e-3) / 1e9 if r["n_spans"] else None
         flops = sum(2.0 * rows * N * Kd for N, Kd in shapes) / len(shapes)
@@ -355,9 +553,14 @@ def main():
                               "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
                               "traffic": measured_traffic(layout_name, rows),
-                              "bytes_per_launch": per_launch, "avg_launch_ms": avg_ms, "launches_timed": r["n_spans"],
-                              "mfma_tflops": flops / (avg_ms * 1e-3) / 1e12 if r["n_spans"] else None},
-                    roofline_attn={"kernel": "k_attn_mfma", "bound": "hbm",
+                              "bytes_per_launch": per_launch, "bytes_per_launch_all_fp32_out": per_launch_fp32,
+                              "avg_launch_ms": avg_ms, "launches_timed": r["n_spans"],
+                              "frac_of_sustained_6200": (achieved / HBM_SUSTAINED_GBS) if achieved else None,
+                              "mfma_tflops": flops / (avg_ms * 1e-3) / 1e12 if r["n_spans"] else None,
+                              "mfma_frac": flops / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if r["n_spans"] else None,
+                              "mfma_frac_of_sustained_1880": flops / (avg_ms * 1e-3) / 1e12 / MFMA_SUSTAINED_TFLOPS
+                              if r["n_spans"] else None},
+                    roofline_attn={"kernel": "k_attn_ring", "bound": "hbm",
                                    "achieved": attn_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else None,
                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "bytes_per_launch": attn_bytes,
                                    "avg_launch_ms": attn_ms, "kv_len": Lnow},
@@ -428,11 +631,59 @@ def main():
                                                      "tau_1.74": round(1.74 / e["esp_step_cost_ratio"], 3),
                                                      "note": "derived from the paper's tau, not measured here"}
         out["bc_sweep_per_node"] = sweep
+    if not args.no_planted:
+        out["planted_acceptance"] = planted_acceptance(B, torch, main_r["dec"])
+        out["planted_acceptance"]["layout"] = args.layout
+        out["planted_acceptance"]["speedup_over_ar"] = out["planted_acceptance"]["tokens_per_s"] * ar_ms / 1e3
+        if alt_r is not None:
+            pa = planted_acceptance(B, torch, alt_r["dec"])
+            pa["layout"] = alt_name
+            pa["speedup_over_ar"] = pa["tokens_per_s"] * ar_ms / 1e3
+            out["alt_layout"]["planted_acceptance"] = pa
     if not args.no_stages:
         out["stage_rooflines"] = stage_rooflines(B, synth, torch, shape, holder["eng"].lm_head)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, synth, shape, weights, n_nodes, k, K, kp, L,
                                            layouts[args.layout])
+    if not args.no_configs:
+        del main_r, alt_r
+        cfgs = {}
+        # configs[3]: long context, full-depth Llama step; the root-chain layout (68 rows) is the headline
+        holder["eng"].close()
+        holder.clear()
+        torch.cuda.empty_cache()
+        h4 = {"eng": B.Engine(shape, weights, 1, 320, 32768 + 2048)}
+        cfgs["config4_llama3_8b_kv32768"] = [
+            run_case(B, decode, synth, torch, shape, weights, h4, lay, 64, 4, 8, 10, [32768], 10, 2)
+            for lay in (B.LAYOUT_ROOT_CHAIN, B.LAYOUT_PER_NODE)]
+        h4["eng"].close()
+        del h4
+        torch.cuda.empty_cache()
+        # configs[4]: batch 16, ragged cache lengths and node counts (seeds as in the parity test)
+        lens5 = (512 + synth.uniform_ints(16, 7681, 3, 0)).tolist()
+        nodes5 = (32 + synth.uniform_ints(16, 97, 4, 0)).tolist()
+        cfgs["config5_llama3_8b_batch16_ragged"] = []
+        for lay in (B.LAYOUT_ROOT_CHAIN, B.LAYOUT_PER_NODE):
+            h5 = {}
+            cfgs["config5_llama3_8b_batch16_ragged"].append(
+                run_case(B, decode, synth, torch, shape, weights, h5, lay, 128, 4, 8, 10, lens5, 6, 2, node_counts=nodes5))
+            h5["eng"].close()
+            del h5
+            torch.cuda.empty_cache()
+        del weights
+        torch.cuda.empty_cache()
+        # configs[2]: Qwen3-8B shape (QK-norm, 36 layers, 151936-token vocabulary), EMA mask update
+        qshape = synth.SHAPES["qwen3_8b"]
+        qw = synth.make_weights(qshape, seed=1, device="cuda")
+        h3 = {}
+        decode.EspDecoder.default_max_rows = 96 * 6
+        cfgs["config3_qwen3_8b_kv4096"] = [
+            run_case(B, decode, synth, torch, qshape, qw, h3, lay, 96, 5, 10, 12, [4096], 10, 2, ema=0.1)
+            for lay in (B.LAYOUT_PER_NODE, B.LAYOUT_ROOT_CHAIN)]
+        h3["eng"].close()
+        del h3, qw
+        torch.cuda.empty_cache()
+        out["configs"] = cfgs
     print(json.dumps(out))
 
 
