@@ -169,23 +169,35 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
       __syncthreads();
       return;
     }
-    // One chunk of matrix work from `stage`
-    auto chunk = [&](int stage) {
+    // The computing waves run the chunks as one stream of 16-wide steps.  Fragment reads go one MFMA
+    // group ahead of their use, also across the chunk boundary: when the last step of a chunk starts,
+    // all of that chunk's fragments are in registers, so the barrier that says "chunk c + 1 has landed"
+    // sits there, and the last step's MFMAs cover the first reads of chunk c + 1.  (For the loading
+    // waves the same barrier says that nobody reads chunk c's stage any more.)
+    bf16x8_t af[2][MT], wf[2][NB];
+    auto read_frag = [&](int stage, int st, int i) {
       const unsigned char* sa = lds + stage * STAGE;
-      const unsigned char* sw = sa + A_STAGE + wave_u * NB * 4096 + lane * 16;
-      bf16x8_t af[2][MT], wf[2][NB];
+      af[st & 1][i] = *reinterpret_cast<const bf16x8_t*>(sa + i * 4096 + a_rd[st]);
+      if (i < NB)
+        wf[st & 1][i] = *reinterpret_cast<const bf16x8_t*>(sa + A_STAGE + (wave_u * NB + i) * 4096 + lane * 16 + st * 1024);
+    };
+    static_assert(NB <= MT, "weight fragments ride along with the first NB activation fragments");
+    if (nc > 0) {                                         // (uniform: the loading waves count the same barriers)
+      __syncthreads();                                    // chunk 0 has landed
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(sa + i * 4096 + a_rd[0]);
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) wf[0][nb] = *reinterpret_cast<const bf16x8_t*>(sw + nb * 4096);
+      for (int i = 0; i < MT; ++i) read_frag(0, 0, i);
+    }
+    int stage = 0;
+    for (int c = 0; c < nc; ++c) {
+      const int stage_next = stage + 1 == RING ? 0 : stage + 1;
+      const bool more = c + 1 < nc;
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
+        if (st == 3 && more) __syncthreads();             // chunk c + 1 has landed; chunk c is in registers
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
-          if (st < 3) {
-            af[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(sa + i * 4096 + a_rd[st + 1]);
-            if (i < NB) wf[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(sw + i * 4096 + (st + 1) * 1024);
-          }
+          if (st < 3) read_frag(stage, st + 1, i);
+          else if (more) read_frag(stage_next, 0, i);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
@@ -193,12 +205,7 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-    };
-    int stage = 0;
-    for (int c = 0; c < nc; ++c) {
-      __syncthreads();                                    // chunk c has landed; everyone is done with chunk c - 1
-      chunk(stage);
-      stage = stage + 1 == RING ? 0 : stage + 1;
+      stage = stage_next;
     }
     __syncthreads();                                      // the epilogues reuse the LDS
   } else {
@@ -330,10 +337,82 @@ __device__ __forceinline__ void gemm_bf16_body(unsigned char* lds, const bf16_t*
       }
     }
   }
-  if (EPI == 1 || EPI == 3) {
-    // arg-max epilogue (LM head at the tree rows; needs splits == 1): per row the maximum over
-    // this workgroup's columns, lowest column on ties.  `out` receives [n_tiles][M] pairs
-    // (value, column as int bits); the logits themselves are never written.
+  if ((EPI == 1 || EPI == 3) && RING > 0) {
+    // arg-max epilogue of the large tile (LM head at many tree rows; needs splits == 1): per row the
+    // maximum over this workgroup's columns, lowest column on ties; `out` receives [n_tiles][M] pairs
+    // (value, column as int bits) and the logits themselves are never written.  A lane holds one
+    // column of 16 rows per MFMA tile, so the maximum along a row is a reduction across lanes: each
+    // wave transposes its tile through its own slice of the (now idle) ring and every lane then
+    // scans whole rows with 16-byte reads.  (Butterfly shuffles cost ten LDS round trips per row.)
+    constexpr int ROWS = MT * 32, LD = 36;                  // 36 words: 16-byte aligned rows, 2-way conflicts at most
+    float* tr = reinterpret_cast<float*>(lds) + wave * (ROWS * LD);
+    float best[(ROWS + 63) / 64];
+    int bi[(ROWS + 63) / 64];
+#pragma unroll
+    for (int q = 0; q < (ROWS + 63) / 64; ++q) { best[q] = -INFINITY; bi[q] = 0x7fffffff; }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int nbase = n0 + nb * 32;
+      if (draw_pos) {   // sample matching: the row draws its next token, arg-max of logit + Gumbel noise
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int rl = i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+            tr[rl * LD + lr] = acc[i][nb][v] +
+                               gumbel_noise(seed, (uint32_t)draw_pos[min(m0 + rl, M - 1)], (uint32_t)(nbase + lr));
+          }
+      } else {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) tr[(i * 32 + 8 * (v >> 2) + 4 * lg + (v & 3)) * LD + lr] = acc[i][nb][v];
+      }
+      if (nbase < N) {
+#pragma unroll
+        for (int q = 0; q < (ROWS + 63) / 64; ++q) {
+          const int rl = q * 64 + lane;
+          if (rl < ROWS) {
+            f32x4_t x[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) x[c] = *reinterpret_cast<const f32x4_t*>(tr + rl * LD + 4 * c);
+#pragma unroll
+            for (int c = 0; c < 32; ++c)   // columns ascend: ties keep the lower one
+              if (x[c >> 2][c & 3] > best[q]) { best[q] = x[c >> 2][c & 3]; bi[q] = nbase + c; }
+          }
+        }
+      }
+    }
+    __syncthreads();                                        // every wave is done with its slice
+    float* red = reinterpret_cast<float*>(lds);             // [4 waves][ROWS][2]
+#pragma unroll
+    for (int q = 0; q < (ROWS + 63) / 64; ++q) {
+      const int rl = q * 64 + lane;
+      if (rl < ROWS) {
+        red[(wn * ROWS + rl) * 2 + 0] = best[q];
+        red[(wn * ROWS + rl) * 2 + 1] = __int_as_float(bi[q]);
+      }
+    }
+    __syncthreads();
+    for (int rl = tid; rl < ROWS; rl += 256) {
+      float bv = red[rl * 2];
+      int bj = __float_as_int(red[rl * 2 + 1]);
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float ov = red[(w * ROWS + rl) * 2];
+        const int oi = __float_as_int(red[(w * ROWS + rl) * 2 + 1]);
+        if (ov > bv || (ov == bv && oi < bj)) { bv = ov; bj = oi; }
+      }
+      const int m = mt0 + rl;
+      float* pairs = EPI == 3 ? out2 : out;
+      if (m < M) {
+        pairs[((size_t)ni * M + m) * 2 + 0] = bv;
+        pairs[((size_t)ni * M + m) * 2 + 1] = __int_as_float(bj);
+      }
+    }
+  } else if (EPI == 1 || EPI == 3) {
+    // arg-max epilogue of the small tiles: the same result by butterfly shuffles (their LDS holds no
+    // transposed tile)
     float* red = reinterpret_cast<float*>(lds);            // [4 waves][MT*32 rows][2]
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
