@@ -416,6 +416,32 @@ def stage_rooflines(B, synth, torch, shape, lm_head_packed):
             "unit": "GB/s", "frac": byts / ms / 1e6 / HBM_PEAK_GBS,
             "frac_of_sustained_6200": byts / ms / 1e6 / HBM_SUSTAINED_GBS, "bytes_per_launch": byts, "avg_launch_ms": ms,
             "mfma_tflops": flops / ms / 1e9, "mfma_frac": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+    # tree building (Alg. 1) at block complexity 30 and 60 (6 and 12 nodes, k = 4): the dynamic tree,
+    # a fixed tree built in full on every call (two width lists alternate on one block, which
+    # defeats the reuse) and the same fixed tree with its rows reused (only the tokens are written)
+    k, kp = 4, 10
+    ids = torch.stack([torch.randperm(sh.vocab, device="cuda")[:kp] for _ in range(k)]).to(torch.int32)[None].contiguous()
+    ps = torch.sort(torch.rand((1, k, kp), device="cuda"), dim=-1, descending=True).values.contiguous()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    n_lists, n_emit = torch.full((1,), k, **i32), torch.ones(1, **i32)
+    emit = torch.zeros((1, B.MAX_MASKS + 1), **i32)
+    out["tree_build_us"] = {}
+    for nodes, wa, wb in ((6, [2, 1, 1, 1], [1, 2, 1, 1]), (12, [5, 3, 2, 1], [5, 3, 1, 2])):
+        blk = B.BlockBuffers(1, nodes * (k + 1), k, B.LAYOUT_PER_NODE)
+        dyn = B.tree_params(nodes, k, 8, 0, True, False, B.LAYOUT_PER_NODE)
+        sa = B.tree_params(nodes, k, 8, 1, True, False, B.LAYOUT_PER_NODE, wa)
+        sb = B.tree_params(nodes, k, 8, 1, True, False, B.LAYOUT_PER_NODE, wb)
+        flip = [0]
+
+        def alternate():
+            flip[0] ^= 1
+            eng.build_prune_tree(sa if flip[0] else sb, ids, ps, kp, n_lists, n_emit, emit, blk)
+        t_dyn = time_gpu(torch, lambda: eng.build_prune_tree(dyn, ids, ps, kp, n_lists, n_emit, emit, blk), 50, warm=3)
+        t_full = time_gpu(torch, alternate, 50, warm=3)
+        t_reuse = time_gpu(torch, lambda: eng.build_prune_tree(sa, ids, ps, kp, n_lists, n_emit, emit, blk), 50, warm=3)
+        out["tree_build_us"][f"block_complexity_{nodes * (k + 1)}"] = {
+            "dynamic": round(t_dyn * 1e3, 2), "static_built_in_full": round(t_full * 1e3, 2),
+            "static_rows_reused": round(t_reuse * 1e3, 2)}
     assert eng.device_status() == 0
     eng.close()
     del eng, kv, kf, vf, w

@@ -504,10 +504,37 @@ esp_status esp_build_prune_tree(esp_ctx* c, const esp_tree_params* p, const int3
     }
     if (total > 4096) return ESP_ECAPACITY;
   }
+  // a fixed tree's rows are built once per block: later calls with the same parameters on the
+  // same block only write its tokens (the kernel still checks, per sequence, that the block
+  // holds a tree of that size and that every list is there, and builds in full otherwise)
+  bool reuse = false;
+  uint64_t sig = 0;
+  if (p->static_widths[0] > 0) {
+    sig = 0x9E3779B97F4A7C15ull;
+    auto mix = [&](uint64_t v) { sig = (sig ^ v) * 0x100000001B3ull; };
+    mix((uint64_t)p->k); mix((uint64_t)p->layout); mix((uint64_t)p->prune_parent); mix((uint64_t)p->prune_last);
+    mix((uint64_t)Kp); mix((uint64_t)next->batch); mix((uint64_t)next->rows_per_seq);
+    for (int i = 0; i < p->k; ++i) mix((uint64_t)p->static_widths[i]);
+  }
+  esp_ctx::StaticTreeSlot* slot = nullptr;
+  for (auto& sl : c->static_trees)
+    if (sl.tok == next->tok) slot = &sl;
+  if (p->static_widths[0] > 0) {
+    reuse = slot && slot->sig == sig;
+    if (!slot) {   // take a free slot, else the first one
+      slot = &c->static_trees[0];
+      for (auto& sl : c->static_trees)
+        if (!sl.tok) { slot = &sl; break; }
+    }
+    slot->tok = next->tok;
+    slot->sig = sig;
+  } else if (slot) {
+    slot->tok = nullptr;      // a dynamic tree overwrites the block's rows
+  }
   ESP_PROF(ESP_SITE_TREE);
   ESP_HIP(launch_build_tree(c->stream, *p, next->batch, topk_id, topk_p, Kp, n_lists, n_emit, emit_tok,
                             next->rows_per_seq, next->anc_words, next->n_rows, next->n_nodes, next->tok,
-                            next->parent, next->depth, next->mask_j, next->attach, next->anc, c->status));
+                            next->parent, next->depth, next->mask_j, next->attach, next->anc, c->status, reuse));
   return ESP_OK;
 }
 
@@ -515,6 +542,8 @@ esp_status esp_block_from_tree(esp_ctx* c, esp_block* blk) {
   if (!c) return ESP_EINVAL;
   esp_status st = check_block(c, blk);
   if (st != ESP_OK) return st;
+  for (auto& sl : c->static_trees)
+    if (sl.tok == blk->tok) sl.tok = nullptr;     // the block's rows are rewritten
   ESP_HIP(launch_block_from_tree(c->stream, blk->batch, blk->rows_per_seq, blk->k_masks, blk->layout, blk->anc_words,
                                  blk->n_rows, blk->n_nodes, blk->tok, blk->parent, blk->depth, blk->mask_j,
                                  blk->attach, blk->anc, c->status));

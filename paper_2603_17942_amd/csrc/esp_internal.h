@@ -203,7 +203,7 @@ hipError_t launch_build_tree(hipStream_t st, const esp_tree_params& p, int batch
                              const float* topk_p, int kp, const int32_t* n_lists, const int32_t* n_emit,
                              const int32_t* emit_tok, int rows_per_seq, int anc_words, int32_t* n_rows,
                              int32_t* n_nodes, int32_t* tok, int32_t* parent, int32_t* depth, int32_t* mask_j,
-                             int32_t* attach, uint64_t* anc, int32_t* status);
+                             int32_t* attach, uint64_t* anc, int32_t* status, bool reuse);
 
 // ---- context --------------------------------------------------------------------------------------
 struct esp_ctx {
@@ -230,6 +230,10 @@ struct esp_ctx {
   int32_t *idx_c, *idx_d;       // draw positions per block row / per node-list entry
   const void* lm_cache_hidden = nullptr;
   int lm_cache_rows = 0;
+  // blocks that hold the rows of a fixed tree built with these parameters (esp_build_prune_tree
+  // then only rewrites their tokens): identity = address of the block's token array
+  struct StaticTreeSlot { const void* tok = nullptr; uint64_t sig = 0; };
+  StaticTreeSlot static_trees[4];
   float* rope_tab;   // [Mmax][hd/2][2] cos, sin
   float* logits;     // fp32 [logits_rows][vocab]
   float* topk_scratch;

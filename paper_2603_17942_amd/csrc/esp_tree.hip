@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int
                                                     const int32_t* __restrict__ emit_tok, int rows_per_seq,
                                                     int anc_words, int32_t* n_rows, int32_t* n_nodes, int32_t* tok,
                                                     int32_t* parent, int32_t* depth, int32_t* mask_j,
-                                                    int32_t* attach, uint64_t* anc, int32_t* status) {
+                                                    int32_t* attach, uint64_t* anc, int32_t* status, int reuse) {
   extern __shared__ __align__(16) unsigned char raw[];
   TreeLds& s = *reinterpret_cast<TreeLds*>(raw);
   __shared__ int s_bad;
@@ -328,6 +328,45 @@ __global__ __launch_bounds__(256) void k_build_tree(esp_tree_params p, const int
   if (ne < 1 || ne > ESP_MAX_MASKS + 1) {   // sequence skipped upstream
     if (tid == 0) { n_rows[seq] = 0; n_nodes[seq] = 0; atomicOr(status, ESP_DEV_BAD_TREE); }
     return;
+  }
+  if (is_static && reuse && depth_limit == p.k) {
+    // Fixed tree whose rows this block already holds (Sec. 4.3: the descriptor of a static tree is
+    // built once): the shape -- root, K_1 children, K_i children under the first node of depth i - 1
+    // -- does not depend on the lists, so parents, depths, mask rows and ancestor sets stay and
+    // only the tokens are written.  A thread per node walks the chain of first children down to its
+    // own depth.  If a list runs out of surviving entries the shape would change: then (all threads
+    // agree first, before anything is written) the full build below runs instead.
+    int n_static = 1;
+    for (int i = 0; i < p.k; ++i) n_static += p.static_widths[i];
+    if (n_nodes[seq] == n_static) {
+      const int root = emit_tok[(size_t)seq * (ESP_MAX_MASKS + 1) + ne - 1];
+      int my_depth = 0, my_j = 0, base = 1;
+      for (int i = 1; i <= p.k; ++i) {
+        if (tid >= base && tid < base + p.static_widths[i - 1]) { my_depth = i; my_j = tid - base; }
+        base += p.static_widths[i - 1];
+      }
+      const bool live = tid < n_static;
+      int ok = 1, par_tok = root, my_tok = root;
+      for (int i = 1; i <= p.k && live && my_depth >= i; ++i) {
+        const int32_t* li = topk_id + ((size_t)seq * p.k + (i - 1)) * kp;
+        const int want = my_depth == i ? my_j : 0;       // own entry at the own depth, the first child above
+        int cnt = 0, pick = -1;
+        for (int c = 0; c < kp; ++c) {
+          const int t = li[c];
+          if (t < 0) break;
+          if (p.prune_parent && t == par_tok) continue;
+          if (p.prune_last && i >= 2 && t == root) continue;
+          if (cnt == want) { pick = t; break; }
+          ++cnt;
+        }
+        if (pick < 0) ok = 0;
+        if (my_depth == i) my_tok = pick; else par_tok = pick;
+      }
+      if (!__syncthreads_or(!ok)) {
+        if (live) tok[r0 + tid] = my_tok;
+        return;
+      }
+    }
   }
   if (tid == 0) {
     s.tok[0] = emit_tok[(size_t)seq * (ESP_MAX_MASKS + 1) + ne - 1];
@@ -540,7 +579,7 @@ hipError_t launch_build_tree(hipStream_t st, const esp_tree_params& p, int batch
                              const float* topk_p, int kp, const int32_t* n_lists, const int32_t* n_emit,
                              const int32_t* emit_tok, int rows_per_seq, int anc_words, int32_t* n_rows,
                              int32_t* n_nodes, int32_t* tok, int32_t* parent, int32_t* depth, int32_t* mask_j,
-                             int32_t* attach, uint64_t* anc, int32_t* status) {
+                             int32_t* attach, uint64_t* anc, int32_t* status, bool reuse) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_build_tree),
@@ -550,6 +589,6 @@ hipError_t launch_build_tree(hipStream_t st, const esp_tree_params& p, int batch
   }
   hipLaunchKernelGGL(k_build_tree, dim3(batch), dim3(256), sizeof(TreeLds), st, p, topk_id, topk_p, kp, n_lists,
                      n_emit, emit_tok, rows_per_seq, anc_words, n_rows, n_nodes, tok, parent, depth, mask_j,
-                     attach, anc, status);
+                     attach, anc, status, reuse ? 1 : 0);
   return hipGetLastError();
 }

@@ -270,6 +270,34 @@ def test_build_prune_tree_bit_exact(B, tiny_engine, Bn, k, K, kp, width, layout,
         assert nxt.tok[r0:r0 + n].tolist() == tok.tolist()
         assert nxt.parent[r0:r0 + n].tolist() == par.tolist()
         check_block(nxt, b, tok, par, k, layout)
+    if static is None:
+        return
+    # Fixed tree, same block again (Sec. 4.3: its rows are built once; later calls only write tokens):
+    # new lists and roots, every sequence with all k lists -- then a call in which a list of sequence
+    # 1 runs out of entries, so that its tree is smaller and must be rebuilt in full -- then full lists
+    # again.  Every call is checked against the oracle like the first one.
+    for rnd in range(3):
+        for b in range(batch):
+            ids[b], ps[b] = random_lists(rng, k, kp, vocab_small)
+        n_lists[:] = k
+        if rnd == 1:
+            ids[1, 0, 1:] = -1                       # depth 1 of sequence 1 has a single entry
+            ps[1, 0, 1:] = 0.0
+        emit[:, 0] = rng.integers(0, vocab_small, size=batch)
+        n_emit[:] = 1
+        eng.build_prune_tree(params, dev(ids), dev(ps), kp, dev(n_lists), dev(n_emit), dev(emit), nxt)
+        assert eng.device_status() == 0
+        for b in range(batch):
+            # (a negative id ends a list on the device; the oracle is handed the list cut there)
+            li = [ids[b, i][:1] if (rnd == 1 and b == 1 and i == 0) else ids[b, i] for i in range(k)]
+            lp = [ps[b, i][:1] if (rnd == 1 and b == 1 and i == 0) else ps[b, i] for i in range(k)]
+            tok, par, _ = O.build_prune_tree(op, li, lp, int(emit[b, 0]), n_depths=k)
+            r0 = b * rows
+            n = int(nxt.n_nodes[b])
+            assert n == len(tok), (rnd, b, n, len(tok))
+            assert nxt.tok[r0:r0 + n].tolist() == tok.tolist(), (rnd, b)
+            assert nxt.parent[r0:r0 + n].tolist() == par.tolist(), (rnd, b)
+            check_block(nxt, b, tok, par, k, layout)
 
 
 def test_build_prune_tree_with_every_probability_tied(B, tiny_engine):
