@@ -156,7 +156,10 @@ def run_case(B, decode, synth, torch, shape, weights, eng_holder, layout, n_node
             eng.kv_store(dec.kv, l, b, 0, kb, vb)
     del kf, vf
     dec.kv.set_len(lens)
-    eng.mask_mean(synth.make_prompt(256, shape.vocab, seed=2).to("cuda", torch.int32), k, dec.mask_embed)
+    eng.mask_mean(synth.make_prompt(256, shape.vocab, seed=2).to("cuda", torch.int32), k,
+                  dec.mask_embed[0] if dec.per_seq_masks else dec.mask_embed)
+    if dec.per_seq_masks:
+        dec.mask_embed.copy_(dec.mask_embed[0].clone())
     counts = node_counts if node_counts is not None else [n_nodes] * batch
     trees = [synth.make_random_tree(counts[b], k, shape.vocab, seed=7 + b) for b in range(batch)]
     dec.set_tree([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])

@@ -195,7 +195,7 @@ esp_status esp_set_sampling(esp_ctx *ctx, int32_t enabled, uint32_t seed);
  * K/V of the rows written to cache slots len[b]+row, tree-masked grouped-query attention over
  * cache slots [0,len[b]) plus the block rows in the row's ancestor bitset (App. C), output
  * projection, SwiGLU MLP; final RMSNorm.
- *   mask_embed  device [k_masks, d_model], model dtype
+ *   mask_embed  device [k_masks, d_model], model dtype ([batch, k_masks, d_model] after esp_set_mask_batch)
  *   hidden_out  device [batch*rows_per_seq, d_model], model dtype: final-norm hidden states
  *   node_argmax device [batch*rows_per_seq] int32: argmax over the vocabulary of the LM head at
  *               node rows (lowest id on ties); entries of mask rows are left untouched
@@ -239,6 +239,13 @@ esp_status esp_mask_topk(esp_ctx *ctx, const esp_block *blk, const int32_t *star
  * pruning rule, P(child) = P(parent) * p as one fp32 product; between depths the node set is the
  * B-i most probable not-yet-used candidates; the tree is the root plus the B-1 most probable of
  * all candidates (ties: earlier created first).  Writes every array of `next` for each sequence.
+ * Fixed trees (static_widths set; Sec. 4.3): root, K_1 children, K_i children under the first node
+ * of depth i-1.  Their rows do not depend on the lists, so they are built once per block: the
+ * context remembers which blocks (by the address of `tok`) hold the rows of which fixed tree, and a
+ * later call with the same parameters writes only the tokens (per sequence the kernel still checks
+ * that the block holds a tree of that size and that no list runs out, and builds in full if not).
+ * A caller that writes the structure arrays of such a block itself must pass the block through
+ * esp_block_from_tree before the next esp_build_prune_tree.
  * Errors: EINVAL (B, k, K, Kp out of range; k != next->k_masks), ECAPACITY (rows of the tree
  * exceed next->rows_per_seq). */
 esp_status esp_build_prune_tree(esp_ctx *ctx, const esp_tree_params *p, const int32_t *topk_id,
@@ -258,6 +265,17 @@ esp_status esp_mask_mean(esp_ctx *ctx, const int32_t *tokens, int32_t n_tokens, 
                          void *mask_embed);
 esp_status esp_mask_ema(esp_ctx *ctx, const int32_t *n_emit, const int32_t *emit_tok, float lambda,
                         int32_t k, void *mask_embed);
+
+/* Mask vectors per sequence (Eq. 4 and Eq. 5 are stated per generation).  esp_set_mask_batch with
+ * per_sequence != 0 makes esp_tree_forward read the mask rows of sequence b from
+ * mask_embed + b * k_masks * d_model, i.e. mask_embed is device [batch, k_masks, d_model]; 0 (the state a
+ * new context is in) is the shared [k_masks, d_model] form.  Host-side state only: takes effect for the calls
+ * enqueued after it.  esp_mask_ema_batch is Eq. 5 for that form: the vectors of sequence b move towards
+ * the embedding of b's own last emitted token (n_emit[b], emit_tok[b][.]); sequences that emitted nothing
+ * keep theirs.  The initialisers above write one [k, d_model] slice per call: pass mask_embed + b * k * d_model. */
+esp_status esp_set_mask_batch(esp_ctx *ctx, int32_t per_sequence);
+esp_status esp_mask_ema_batch(esp_ctx *ctx, int32_t batch, const int32_t *n_emit, const int32_t *emit_tok,
+                              float lambda, int32_t k, void *mask_embed);
 
 /* The two other initialisations of the mask-design ablation (Sec. 4) and the out-of-distribution
  * rows of the appendix table on mask initialisation.

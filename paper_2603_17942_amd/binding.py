@@ -58,7 +58,7 @@ class TreeParams(C.Structure):
 
 EXPORTS = ["esp_status_str", "esp_workspace_bytes", "esp_create", "esp_destroy", "esp_last_device_status",
            "esp_tree_forward", "esp_verify_accept", "esp_mask_topk", "esp_build_prune_tree",
-           "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_mask_last_k", "esp_mask_gaussian", "esp_kv_store", "esp_kv_load",
+           "esp_block_from_tree", "esp_mask_mean", "esp_mask_ema", "esp_set_mask_batch", "esp_mask_ema_batch", "esp_mask_last_k", "esp_mask_gaussian", "esp_kv_store", "esp_kv_load",
            "esp_gemm_scratch_bytes", "esp_gemm", "esp_gemm_argmax_scratch_bytes", "esp_gemm_argmax", "esp_attn_tree", "esp_softmax_topk_scratch_bytes",
            "esp_softmax_topk", "esp_softmax_topk_static", "esp_profile_enable", "esp_profile_read", "esp_pack_weight", "esp_set_sampling"]
 SITES = {"gemm_layer": 0, "attn": 1, "attn_merge": 2, "lm_head": 3, "topk": 4, "tree": 5, "glue": 6}
@@ -96,6 +96,8 @@ def load_library() -> C.CDLL:
     lib.esp_block_from_tree.argtypes = [_vp, P(Block)]
     lib.esp_mask_mean.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.esp_mask_ema.argtypes = [_vp, _vp, _vp, _f32, _i32, _vp]
+    lib.esp_set_mask_batch.argtypes = [_vp, _i32]
+    lib.esp_mask_ema_batch.argtypes = [_vp, _i32, _vp, _vp, _f32, _i32, _vp]
     lib.esp_mask_last_k.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.esp_mask_gaussian.argtypes = [_vp, _vp, _f32, _i32, _vp]
     lib.esp_kv_store.argtypes = [_vp, P(Kv), _i32, _i32, _i32, _i32, _vp, _vp]
@@ -314,6 +316,8 @@ class Engine:
                      hidden_out: torch.Tensor, node_argmax: Optional[torch.Tensor],
                      logits_dbg: Optional[torch.Tensor] = None):
         b, k = blk.struct(), kv.struct()
+        if mask_embed is not None:       # [batch, k, d]: one set of mask vectors per sequence; [k, d]: shared
+            self.set_mask_batch(mask_embed.dim() == 3)
         _check(self.lib.esp_tree_forward(self.ctx, C.byref(b), _ptr(mask_embed), C.byref(k), _ptr(hidden_out),
                                          _ptr(node_argmax), _ptr(logits_dbg)), "esp_tree_forward")
 
@@ -357,6 +361,13 @@ class Engine:
     def mask_ema(self, n_emit, emit_tok, lam: float, k: int, mask_embed: torch.Tensor):
         _check(self.lib.esp_mask_ema(self.ctx, _ptr(n_emit), _ptr(emit_tok), lam, k, _ptr(mask_embed)),
                "esp_mask_ema")
+
+    def set_mask_batch(self, per_sequence: bool):
+        _check(self.lib.esp_set_mask_batch(self.ctx, int(bool(per_sequence))), "esp_set_mask_batch")
+
+    def mask_ema_batch(self, batch: int, n_emit, emit_tok, lam: float, k: int, mask_embed: torch.Tensor):
+        _check(self.lib.esp_mask_ema_batch(self.ctx, batch, _ptr(n_emit), _ptr(emit_tok), lam, k, _ptr(mask_embed)),
+               "esp_mask_ema_batch")
 
     def kv_store(self, kv: KvCache, layer: int, seq: int, first_slot: int, k_rows, v_rows):
         k = kv.struct()

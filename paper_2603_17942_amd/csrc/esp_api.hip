@@ -339,7 +339,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
 
   { ESP_PROF(ESP_SITE_GLUE);
   ESP_HIP(launch_embed(s, dt, bd, kd, c->embed, mask_embed, c->h, d, m.vocab, c->rope_tab, hd, m.rope_theta,
-                       c->status));
+                       c->status, c->mask_per_seq ? (size_t)blk->k_masks * d : 0));
   ESP_HIP(launch_residual_norm(s, dt, c->h, nullptr, 0, M, d, c->norm_attn[0], m.rms_eps, c->xn)); }
   for (int l = 0; l < m.n_layers; ++l) {
     { ESP_PROF(ESP_SITE_GEMM_LAYER);
@@ -581,7 +581,22 @@ esp_status esp_mask_ema(esp_ctx* c, const int32_t* n_emit, const int32_t* emit_t
                         void* mask_embed) {
   if (!c || !n_emit || !emit_tok || !mask_embed || k < 1 || k > ESP_MAX_MASKS) return ESP_EINVAL;
   ESP_HIP(launch_mask_ema(c->stream, c->m.dtype, c->embed, n_emit, emit_tok, lambda, k, c->m.d_model, c->m.vocab,
-                          mask_embed));
+                          mask_embed, 1));
+  return ESP_OK;
+}
+
+esp_status esp_set_mask_batch(esp_ctx* c, int32_t per_sequence) {
+  if (!c) return ESP_EINVAL;
+  c->mask_per_seq = per_sequence != 0;
+  return ESP_OK;
+}
+
+esp_status esp_mask_ema_batch(esp_ctx* c, int32_t batch, const int32_t* n_emit, const int32_t* emit_tok, float lambda,
+                              int32_t k, void* mask_embed) {
+  if (!c || !n_emit || !emit_tok || !mask_embed || k < 1 || k > ESP_MAX_MASKS) return ESP_EINVAL;
+  if (batch < 1 || batch > c->max_batch) return ESP_EINVAL;
+  ESP_HIP(launch_mask_ema(c->stream, c->m.dtype, c->embed, n_emit, emit_tok, lambda, k, c->m.d_model, c->m.vocab,
+                          mask_embed, batch));
   return ESP_OK;
 }
 

@@ -38,7 +38,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_embed(BlockDev b, KvDev kv, const T* __restrict__ embed,
                                                const T* __restrict__ mask_embed, float* __restrict__ h, int d,
                                                int vocab, float* __restrict__ rope_tab, int hd, float theta,
-                                               int32_t* status) {
+                                               int32_t* status, size_t mask_seq_stride) {
   const int row = blockIdx.x;
   const int seq = row / b.rows_per_seq, r = row % b.rows_per_seq;
   const int nr = b.n_rows[seq];
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void k_embed(BlockDev b, KvDev kv, const T* __
   if (live) {
     int j = b.mask_j[row];
     if (j > 0) {
-      if (j <= b.k_masks) src = mask_embed + (size_t)(j - 1) * d;
+      if (j <= b.k_masks) src = mask_embed + seq * mask_seq_stride + (size_t)(j - 1) * d;
     } else {
       int t = b.tok[row];
       if (t < 0 || t >= vocab) {
@@ -73,10 +73,11 @@ __global__ __launch_bounds__(256) void k_embed(BlockDev b, KvDev kv, const T* __
 
 hipError_t launch_embed(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, const void* embed,
                         const void* mask_embed, float* h, int d, int vocab, float* rope_tab, int hd,
-                        float theta, int32_t* status) {
+                        float theta, int32_t* status, size_t mask_seq_stride) {
   int M = b.batch * b.rows_per_seq;
   ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_embed<T>, dim3(M), dim3(256), 0, st, b, kv, (const T*)embed,
-                                         (const T*)mask_embed, h, d, vocab, rope_tab, hd, theta, status));
+                                         (const T*)mask_embed, h, d, vocab, rope_tab, hd, theta, status,
+                                         mask_seq_stride));
   return hipGetLastError();
 }
 
@@ -479,22 +480,27 @@ template <typename T>
 __global__ void k_mask_ema(const T* __restrict__ embed, const int32_t* __restrict__ n_emit,
                            const int32_t* __restrict__ emit_tok, float lambda, int k, int d, int vocab,
                            T* __restrict__ mask_embed) {
+  // blockIdx.y: the sequence whose vectors ([k, d] at mask_embed + y * k * d) follow its own last
+  // emitted token; a launch with one row of workgroups updates the shared vectors from sequence 0
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= d) return;
-  int ne = n_emit[0];
+  const int seq = blockIdx.y;
+  int ne = n_emit[seq];
   if (ne < 1 || ne > ESP_MAX_MASKS + 1) return;
-  int id = emit_tok[ne - 1];
+  int id = emit_tok[(size_t)seq * (ESP_MAX_MASKS + 1) + ne - 1];
   if (id < 0 || id >= vocab) return;
   float e = to_f32(embed[(size_t)id * d + i]);
+  T* me = mask_embed + (size_t)seq * k * d;
   for (int j = 0; j < k; ++j) {
-    float m = to_f32(mask_embed[(size_t)j * d + i]);
-    mask_embed[(size_t)j * d + i] = from_f32<T>(m + lambda * (e - m));
+    float m = to_f32(me[(size_t)j * d + i]);
+    me[(size_t)j * d + i] = from_f32<T>(m + lambda * (e - m));
   }
 }
 
 hipError_t launch_mask_ema(hipStream_t st, int dtype, const void* embed, const int32_t* n_emit,
-                           const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed) {
-  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_ema<T>, dim3((d + 255) / 256), dim3(256), 0, st, (const T*)embed,
+                           const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed,
+                           int n_seq) {
+  ESP_DISPATCH(dtype, hipLaunchKernelGGL(k_mask_ema<T>, dim3((d + 255) / 256, n_seq), dim3(256), 0, st, (const T*)embed,
                                          n_emit, emit_tok, lambda, k, d, vocab, (T*)mask_embed));
   return hipGetLastError();
 }

@@ -145,7 +145,7 @@ struct KvDev {
 
 hipError_t launch_embed(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, const void* embed,
                         const void* mask_embed, float* h, int d, int vocab, float* rope_tab, int hd,
-                        float theta, int32_t* status);
+                        float theta, int32_t* status, size_t mask_seq_stride);
 hipError_t launch_residual_norm(hipStream_t st, int dtype, float* h, const float* part, int splits, int M,
                                 int d, const void* gain, float eps, void* xn_out);
 hipError_t launch_qkv_post(hipStream_t st, int dtype, const BlockDev& b, const KvDev& kv, int layer,
@@ -171,7 +171,7 @@ size_t mask_gaussian_scratch_floats(int d);
 hipError_t launch_mask_gaussian(hipStream_t st, int dtype, const void* embed, int vocab, int d, const float* z,
                                 float shift, int k, float* scratch, size_t scratch_floats, void* mask_embed);
 hipError_t launch_mask_ema(hipStream_t st, int dtype, const void* embed, const int32_t* n_emit,
-                           const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed);
+                           const int32_t* emit_tok, float lambda, int k, int d, int vocab, void* mask_embed, int n_seq);
 
 // ---- attention (esp_attn.hip) ------------------------------------------------------------------
 struct AttnPlan { int nsplit; int tiles_per_split; };
@@ -232,6 +232,7 @@ struct esp_ctx {
   int lm_cache_rows = 0;
   // blocks that hold the rows of a fixed tree built with these parameters (esp_build_prune_tree
   // then only rewrites their tokens): identity = address of the block's token array
+  bool mask_per_seq = false;    // mask vectors are [batch, k, d] (esp_set_mask_batch)
   struct StaticTreeSlot { const void* tok = nullptr; uint64_t sig = 0; };
   StaticTreeSlot static_trees[4];
   float* rope_tab;   // [Mmax][hd/2][2] cos, sin

@@ -51,7 +51,11 @@ class EspDecoder:
         self.topk_id = torch.zeros((self.batch, self.k, kp), **i32)
         self.topk_p = torch.zeros((self.batch, self.k, kp), dtype=torch.float32, device=device)
         self.n_lists = torch.zeros(self.batch, **i32)
-        self.mask_embed = torch.zeros((self.k, shape.d_model), dtype=dt, device=device)
+        # mask vectors: one [k, d] set per sequence (Eq. 4 / Eq. 5 are per generation); a batch of one
+        # keeps the plain [k, d] form
+        self.per_seq_masks = self.batch > 1
+        self.mask_embed = torch.zeros((self.batch, self.k, shape.d_model) if self.per_seq_masks
+                                      else (self.k, shape.d_model), dtype=dt, device=device)
         self.mask_init = "mean"         # "mean" | "last_k" | "gaussian" (with mask_z [k, d] fp32 or None, mask_shift)
         self.mask_z, self.mask_shift = None, 0.0
         self.logits_dbg = None          # set to a [M, vocab] fp32 tensor to capture logits
@@ -83,15 +87,17 @@ class EspDecoder:
                 done[b] += adv[b]
             self.kv.len.add_(torch.tensor(adv, dtype=torch.int32, device=self.device))
             self.kv.len_bound = max(done)
-        ptok = torch.tensor([int(t) for t in prompts[0]], dtype=torch.int32, device=self.device)
-        if self.mask_init == "mean":            # Eq. 4, the paper's default
-            self.eng.mask_mean(ptok, self.k, self.mask_embed)
-        elif self.mask_init == "last_k":        # Sec. 4 variant a
-            self.eng.mask_last_k(ptok, self.k, self.mask_embed)
-        elif self.mask_init == "gaussian":      # Sec. 4 variant b; mask_z: the caller's normal draws
-            self.eng.mask_gaussian(self.mask_z, self.mask_shift, self.k, self.mask_embed)
-        else:
-            raise ValueError(f"unknown mask_init {self.mask_init!r}")
+        for b in range(self.batch if self.per_seq_masks else 1):
+            ptok = torch.tensor([int(t) for t in prompts[b]], dtype=torch.int32, device=self.device)
+            dst = self.mask_embed[b] if self.per_seq_masks else self.mask_embed
+            if self.mask_init == "mean":            # Eq. 4, the paper's default
+                self.eng.mask_mean(ptok, self.k, dst)
+            elif self.mask_init == "last_k":        # Sec. 4 variant a
+                self.eng.mask_last_k(ptok, self.k, dst)
+            elif self.mask_init == "gaussian":      # Sec. 4 variant b; mask_z: the caller's normal draws
+                self.eng.mask_gaussian(self.mask_z, self.mask_shift, self.k, dst)
+            else:
+                raise ValueError(f"unknown mask_init {self.mask_init!r}")
         self.cur.upload_trees([[int(p[-1])] for p in prompts], [[-1]] * self.batch)
         self.eng.block_from_tree(self.cur)
 
@@ -110,7 +116,10 @@ class EspDecoder:
         e.build_prune_tree(self.params, self.topk_id, self.topk_p, self.kp, self.n_lists, self.n_emit,
                            self.emit_tok, self.nxt)
         if self.ema_lambda != 0.0:
-            e.mask_ema(self.n_emit, self.emit_tok, self.ema_lambda, self.k, self.mask_embed)
+            if self.per_seq_masks:
+                e.mask_ema_batch(self.batch, self.n_emit, self.emit_tok, self.ema_lambda, self.k, self.mask_embed)
+            else:
+                e.mask_ema(self.n_emit, self.emit_tok, self.ema_lambda, self.k, self.mask_embed)
         self.cur, self.nxt = self.nxt, self.cur
         self.kv.len_bound += self.k + 1      # a step commits at most k+1 tokens
 

@@ -229,7 +229,8 @@ def test_batched_step_against_oracle(B, Bn, nodes):
     """Three independent sequences of different cache lengths and tree sizes in one block: every
     entry point handles the batch dimension (small bf16 model, full oracle comparison).  The larger
     case has more than 128 tree rows, so the LM head runs on gathered rows through the large-tile
-    GEMM."""
+    GEMM.  Every sequence has mask vectors of its own (Sec. 3.1: Eq. 4 and Eq. 5 are per generation),
+    and the Eq. 5 update after the step follows each sequence's own last token."""
     from paper_2603_17942_amd import decode
     shape = small_shape(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=512, vocab=2048, n_layers=2,
                         dtype="bf16", rope_theta=5.0e5)
@@ -239,7 +240,8 @@ def test_batched_step_against_oracle(B, Bn, nodes):
     lens = [300, 64, 1000]
     print(f"batched step B={Bn} nodes={nodes}", flush=True)
     params = B.tree_params(Bn, k, K, 0, True, False, layout)
-    dec = decode.EspDecoder(shape, w, params, kp, [l + 512 for l in lens], prefill_chunk=64)
+    lam = 0.25
+    dec = decode.EspDecoder(shape, w, params, kp, [l + 512 for l in lens], prefill_chunk=64, ema_lambda=lam)
     fills = []
     for b in range(3):
         kf, vf = synth.make_kv_fill(shape, lens[b], seed=30 + b, device="cuda")
@@ -249,7 +251,8 @@ def test_batched_step_against_oracle(B, Bn, nodes):
     dec.kv.set_len(lens)
     trees = [synth.make_random_tree(nodes[b], k, shape.vocab, seed=50 + b) for b in range(3)]
     dec.set_tree([t.tolist() for t, _ in trees], [p.tolist() for _, p in trees])
-    masks = synth.normal_like((k, shape.d_model), 0.02, 12, 0, "cuda", torch.bfloat16)
+    masks = synth.normal_like((3, k, shape.d_model), 0.02, 12, 0, "cuda", torch.bfloat16)
+    assert dec.mask_embed.shape == masks.shape
     dec.mask_embed.copy_(masks)
     R = dec.rows_per_seq
     dec.logits_dbg = torch.zeros((3 * R, shape.vocab), dtype=torch.float32, device="cuda")
@@ -267,10 +270,13 @@ def test_batched_step_against_oracle(B, Bn, nodes):
         kf, vf = fills[b]
         st = O.DecodeState([to_np(kf[l]) for l in range(shape.n_layers)], [to_np(vf[l]) for l in range(shape.n_layers)],
                            lens[b], trees[b][0].numpy().astype(np.int64), trees[b][1].numpy().astype(np.int64),
-                           to_np(masks))
+                           to_np(masks[b]))
         res = O.esp_step(m, st, O.TreeParams(B=Bn, k=k, K=K, expand_width=0), layout, kp, "bf16")
         rb = res.logits.shape[0]
         assert rel_err_rows(lg[b * R:b * R + rb], res.logits) <= TOL
+        # Eq. 5 on this sequence's own vectors and its own last emitted token (the GPU's: exact inputs)
+        want_m = O.mask_ema_update(to_np(masks[b]), to_np(w["embed"][emitted[b][-1]]), lam)
+        assert rel_err_rows(to_np(dec.mask_embed[b]), want_m) < 1e-2        # one bf16 rounding
         if all(decisive(res.logits[r]) for r in range(nodes[b])):
             assert emitted[b] == res.emitted
             assert int(dec.star_row[b]) == res.n_star
