@@ -74,6 +74,25 @@ def measured_traffic(layout, rows):
     return None
 
 
+TRACE_SUMMARY = os.path.join(ROOT, "profiles", "esp_step_llama3_8b_kv2048_kernel_trace.txt")
+
+
+def traced_kernel_us(layout, rows):
+    """Mean duration of a layer-projection kernel from the committed rocprofv3 kernel-trace summary of this
+    benchmark (begin-to-end time stamps of the kernels themselves).  None when the summary has no line for
+    this layout and row count."""
+    try:
+        for line in open(TRACE_SUMMARY):
+            if not line.startswith("bench-kernel "):
+                continue
+            kv = dict(f.split("=", 1) for f in line.split()[1:])
+            if kv.get("layout") == layout and int(kv.get("rows", -1)) == rows:
+                return float(kv["gemm_layer_avg_us"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
+
+
 PREFILL_CHUNK = int(os.environ.get("ESP_BENCH_PREFILL_CHUNK", "512"))   # rows per prefill block
 
 
@@ -584,6 +603,7 @@ def main():
                               "traffic": measured_traffic(layout_name, rows),
                               "bytes_per_launch": per_launch, "bytes_per_launch_all_fp32_out": per_launch_fp32,
                               "avg_launch_ms": avg_ms, "launches_timed": r["n_spans"],
+                              "avg_kernel_us_rocprof": traced_kernel_us(layout_name, rows),
                               "frac_of_sustained_6200": (achieved / HBM_SUSTAINED_GBS) if achieved else None,
                               "mfma_tflops": flops / (avg_ms * 1e-3) / 1e12 if r["n_spans"] else None,
                               "mfma_frac": flops / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if r["n_spans"] else None,

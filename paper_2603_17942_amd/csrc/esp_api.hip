@@ -136,26 +136,34 @@ hipEvent_t prof_event(esp_ctx* c) {
   return e;
 }
 
-// Times everything enqueued during its lifetime when the site is enabled; otherwise free.
+// Times everything enqueued during its lifetime when the site is enabled; otherwise free.  With
+// `attach` (a scope around exactly one bf16 GEMM launch) the two events are handed to that launch and
+// carry the kernel's own begin and end; a launch that does not take them leaves the span unrecorded.
 struct ProfScope {
   esp_ctx* c = nullptr;
   hipEvent_t stop = nullptr;
-  ProfScope(esp_ctx* ctx, int site) {
+  bool attached = false;
+  ProfScope(esp_ctx* ctx, int site, bool attach = false) {
     if (!((ctx->prof_mask >> site) & 1u)) return;
     hipEvent_t start = prof_event(ctx);
     stop = prof_event(ctx);
     if (!start || !stop) return;
     c = ctx;
-    (void)hipEventRecord(start, c->stream);
+    attached = attach;
+    if (attach) g_launch_events = LaunchEvents{start, stop};
+    else (void)hipEventRecord(start, c->stream);
     c->prof_open.push_back({site, start, stop});
   }
   ~ProfScope() {
-    if (c) (void)hipEventRecord(stop, c->stream);
+    if (!c) return;
+    if (attached) g_launch_events = LaunchEvents{};
+    else (void)hipEventRecord(stop, c->stream);
   }
 };
 #define ESP_CAT2(a, b) a##b
 #define ESP_CAT(a, b) ESP_CAT2(a, b)
 #define ESP_PROF(site) ProfScope ESP_CAT(prof_scope_, __LINE__)(c, site)
+#define ESP_PROF_KERNEL(site, attach) ProfScope ESP_CAT(prof_scope_, __LINE__)(c, site, attach)
 
 // sums split-K partials in split order into C
 __global__ void k_reduce_splits(const float* __restrict__ part, int splits, size_t n, float* __restrict__ out) {
@@ -342,7 +350,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
                        c->status, c->mask_per_seq ? (size_t)blk->k_masks * d : 0));
   ESP_HIP(launch_residual_norm(s, dt, c->h, nullptr, 0, M, d, c->norm_attn[0], m.rms_eps, c->xn)); }
   for (int l = 0; l < m.n_layers; ++l) {
-    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+    { ESP_PROF_KERNEL(ESP_SITE_GEMM_LAYER, dt == ESP_BF16);
       ESP_HIP(launch_gemm(s, dt, c->xn, nullptr, c->wqkv[l], c->gemm_out, M, nqkv, d, p_qkv, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_qkv_post(s, dt, bd, kd, l, c->gemm_out, p_qkv.splits, M, hq, hkv, hd, m.qk_norm, c->q_norm[l],
@@ -351,12 +359,12 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
       ESP_HIP(launch_attn(s, dt, bd, kd, l, hq, hkv, hd, c->q, c->attn_part, ap)); }
     { ESP_PROF(ESP_SITE_ATTN_MERGE);
       ESP_HIP(launch_attn_merge(s, dt, bd, kd, hq, hkv, hd, c->attn_part, ap, c->attn_out)); }
-    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+    { ESP_PROF_KERNEL(ESP_SITE_GEMM_LAYER, dt == ESP_BF16);
       ESP_HIP(launch_gemm(s, dt, c->attn_out, nullptr, c->wo[l], c->gemm_out, M, d, hq * hd, p_o, pk)); }
     { ESP_PROF(ESP_SITE_GLUE);
       ESP_HIP(launch_residual_norm(s, dt, c->h, c->gemm_out, p_o.splits, M, d, c->norm_mlp[l], m.rms_eps, c->xn)); }
     if (dt == ESP_BF16) {   // gate/up projection with the SwiGLU in its epilogue (interleaved weight rows)
-      ESP_PROF(ESP_SITE_GEMM_LAYER);
+      ESP_PROF_KERNEL(ESP_SITE_GEMM_LAYER, true);
       ESP_HIP(launch_gemm_swiglu(s, c->xn, c->wgu[l], c->act, M, ff, d));
     } else {
       { ESP_PROF(ESP_SITE_GEMM_LAYER);
@@ -364,7 +372,7 @@ esp_status esp_tree_forward(esp_ctx* c, const esp_block* blk, const void* mask_e
       { ESP_PROF(ESP_SITE_GLUE);
         ESP_HIP(launch_swiglu(s, dt, c->gemm_out, p_gu.splits, M, ff, c->act)); }
     }
-    { ESP_PROF(ESP_SITE_GEMM_LAYER);
+    { ESP_PROF_KERNEL(ESP_SITE_GEMM_LAYER, dt == ESP_BF16);
       ESP_HIP(launch_gemm(s, dt, c->act, nullptr, c->wdown[l], c->gemm_out, M, d, ff, p_dn, pk)); }
     const bool last = l + 1 == m.n_layers;
     { ESP_PROF(ESP_SITE_GLUE);

@@ -28,6 +28,8 @@
 // fp32 path (tiny configuration): plain LDS-tiled FMA kernel with bounds checks, row-major weights.
 #include <algorithm>
 
+#include <hip/hip_ext.h>
+
 #include "esp_internal.h"
 
 namespace {
@@ -618,6 +620,17 @@ hipError_t ring_allow_lds() {
   return attr;
 }
 
+// launch, with a profiling scope's events attached to the kernel when there are any
+template <typename Kern, typename... Args>
+void launch_kernel(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+  if (g_launch_events.start) {
+    hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)lds, st, g_launch_events.start, g_launch_events.stop, 0, args...);
+    g_launch_events = LaunchEvents{};
+  } else {
+    hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+  }
+}
+
 template <int MT, int NB, bool TILED = true, int D = (MT * NB >= 8 ? 2 : 4), int EPI = 0>
 hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, const void* W, float* out, int M,
                        int N, int K, const GemmPlan& p, int a_ld = 0, float* out2 = nullptr,
@@ -630,19 +643,20 @@ hipError_t launch_bf16(hipStream_t st, const void* A, const int32_t* a_rows, con
     const hipError_t attr = ring_allow_lds<MT, NB, EPI>();
     if (attr != hipSuccess) return attr;
     const size_t ring_bytes = ring_lds_bytes<MT, NB>();
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), ring_bytes, st, (const bf16_t*)A, a_rows,
-                       (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2, draw_pos, seed);
+    launch_kernel(kern, dim3(per_xcd * 8), dim3(512), ring_bytes, st, (const bf16_t*)A, a_rows, (const bf16_t*)W, out,
+                  M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2, draw_pos, seed);
   } else if constexpr (MT * NB >= 8)
-    hipLaunchKernelGGL((k_gemm_bf16_big<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st,
-                       (const bf16_t*)A, a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles,
-                       a_ld, out2);
+    launch_kernel(k_gemm_bf16_big<MT, NB, D, TILED, EPI>, dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
+                  a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2);
   else
-    hipLaunchKernelGGL((k_gemm_bf16<MT, NB, D, TILED, EPI>), dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A,
-                       a_rows, (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2, draw_pos, seed);
+    launch_kernel(k_gemm_bf16<MT, NB, D, TILED, EPI>, dim3(per_xcd * 8), dim3(256), lds, st, (const bf16_t*)A, a_rows,
+                  (const bf16_t*)W, out, M, N, K, p.splits, p.m_tiles, p.n_tiles, a_ld, out2, draw_pos, seed);
   return hipGetLastError();
 }
 
 }  // namespace
+
+thread_local LaunchEvents g_launch_events;
 
 hipError_t gemm_prepare() {
   hipError_t e = ring_allow_lds<4, 2, 0>();

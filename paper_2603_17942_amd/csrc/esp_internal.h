@@ -205,6 +205,12 @@ hipError_t launch_build_tree(hipStream_t st, const esp_tree_params& p, int batch
                              int32_t* n_nodes, int32_t* tok, int32_t* parent, int32_t* depth, int32_t* mask_j,
                              int32_t* attach, uint64_t* anc, int32_t* status, bool reuse);
 
+// Events a profiling scope hands to the next bf16 GEMM launch: the launch attaches them to the kernel
+// itself (hipExtLaunchKernelGGL), so they carry the kernel's own begin and end time stamps and not the
+// time of two extra event commands around it.
+struct LaunchEvents { hipEvent_t start = nullptr, stop = nullptr; };
+extern thread_local LaunchEvents g_launch_events;
+
 // ---- context --------------------------------------------------------------------------------------
 struct esp_ctx {
   esp_model_desc m;
