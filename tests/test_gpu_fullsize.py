@@ -156,6 +156,86 @@ def test_step_at_full_width_two_layer_cut(B, name, layout, n_nodes, k, K, kp, L)
     dec.eng.close()
 
 
+@pytest.mark.parametrize("name,layout,n_nodes,k,K,kp,L,lam", [
+    ("qwen3_8b", 1, 96, 5, 10, 12, 4096, 0.1),     # configs[2] shape, root chain: 101 rows, EMA on
+    ("llama3_8b", 0, 24, 4, 8, 10, 2048, 0.0),     # configs[1] shape, paper layout at block complexity 120
+])
+def test_four_rolling_steps_at_full_width(B, name, layout, n_nodes, k, K, kp, L, lam):
+    """The first four steps of a generation at full width (2-layer cut): every step runs on what the step
+    before left on the GPU -- the tree it built, the cache with the rows it committed, the mask vectors
+    it updated -- and is checked against the oracle run on exactly that state: logits and hidden states
+    of all rows, the integer chain (arg-max, accepted path, cache length, Top-K' ids, next tree) exactly
+    on the GPU's own logits, the committed K/V rows against the oracle's rows of the accepted path, and
+    the Eq. 5 update.  Before every step the true continuation is planted two levels deep (the token the
+    model itself produces, read from a forward of the same block), so that steps commit several rows and
+    the next step attends to them."""
+    from paper_2603_17942_amd import decode
+    print(f"rolling steps {name} layout={layout} N={n_nodes} k={k} L={L}", flush=True)
+    shape = synth.SHAPES[name].replace(n_layers=2)
+    w = synth.make_weights(shape, seed=1, device="cuda")
+    m = oracle_model(shape, w)
+    params = B.tree_params(n_nodes, k, K, 0, True, False, layout)
+    op = O.TreeParams(B=n_nodes, k=k, K=K, expand_width=0)
+    dec = decode.EspDecoder(shape, w, params, kp, [L + 1024], prefill_chunk=64, ema_lambda=lam)
+    kf, vf = synth.make_kv_fill(shape, L, seed=5, device="cuda")
+    for l in range(shape.n_layers):
+        dec.eng.kv_store(dec.kv, l, 0, 0, kf[l].contiguous(), vf[l].contiguous())
+    dec.kv.set_len([L])
+    tok0, par0 = synth.make_random_tree(n_nodes, k, shape.vocab, seed=7)
+    dec.set_tree([tok0.tolist()], [par0.tolist()])
+    dec.mask_embed.copy_(synth.normal_like((k, shape.d_model), 0.02, 6, 0, "cuda", torch.bfloat16))
+    R = dec.rows_per_seq
+    dec.logits_dbg = torch.zeros((R, shape.vocab), dtype=torch.float32, device="cuda")
+    dec.mask_logits = torch.zeros((1, k, shape.vocab), dtype=torch.float32, device="cuda")
+    committed = 0
+    for step in range(4):
+        # plant the model's own continuation along one path, two levels deep (untimed forwards)
+        n = int(dec.cur.n_nodes[0])
+        tok = dec.cur.tok[:n].cpu().numpy().astype(np.int64)
+        par = dec.cur.parent[:n].cpu().numpy().astype(np.int64)
+        node = 0
+        for _ in range(2):
+            ch = [c for c in range(1, n) if par[c] == node]
+            if not ch:
+                break
+            dec.eng.tree_forward(dec.cur, dec.mask_embed, dec.kv, dec.hidden, dec.node_argmax, None)
+            g = int(dec.node_argmax[node])
+            hit = [c for c in ch if tok[c] == g]
+            c = hit[0] if hit else ch[0]
+            dec.cur.tok[c] = g
+            tok[c] = g
+            node = c
+        # the state the step starts from, as the oracle's input
+        L_now = int(dec.kv.len[0])
+        masks_in = to_np(dec.mask_embed)
+        kc, vc = [], []
+        for l in range(shape.n_layers):
+            kk, vv = dec.eng.kv_load(dec.kv, l, 0, 0, L_now)
+            kc.append(to_np(kk)); vc.append(to_np(vv))
+        dec.step()
+        assert dec.eng.device_status() == 0
+        lg = dec.logits_dbg.cpu().numpy()
+        info = identical_logits_leg(dec, 0, tok, par, k, layout, kp, op, L_now, lg, dec.mask_logits[0].cpu().numpy())
+        blk = O.make_block(tok, par, k, layout)
+        logits, hidden, k_new, v_new = O.tree_forward(m, blk, masks_in, kc, vc, L_now, want_logits_rows=list(range(n)))
+        assert rel_err_rows(lg[:n], logits[:n]) <= TOL, step
+        assert rel_err_rows(to_np(dec.hidden[:blk.n_rows]), hidden) <= TOL, step
+        ne = int(dec.n_emit[0])
+        keep = dec.accepted_row[0, :ne].tolist()
+        for l in range(shape.n_layers):
+            kk, vv = dec.eng.kv_load(dec.kv, l, 0, L_now, ne)
+            assert rel_err_rows(to_np(kk).reshape(ne, -1), k_new[l][keep].reshape(ne, -1)) <= TOL, (step, l)
+            assert rel_err_rows(to_np(vv).reshape(ne, -1), v_new[l][keep].reshape(ne, -1)) <= TOL, (step, l)
+        if lam != 0.0:
+            want_m = O.mask_ema_update(masks_in, to_np(w["embed"][int(dec.emit_tok[0, ne - 1])]), lam)
+            assert rel_err_rows(to_np(dec.mask_embed), want_m) < 1e-2, step
+        committed += ne
+        print(f"  step {step}: L={L_now} nodes={n} {info}", flush=True)
+    assert int(dec.kv.len[0]) == L + committed
+    assert committed >= 8          # planted paths were accepted: at least two extra rows in most steps
+    dec.eng.close()
+
+
 def test_long_context_attention_sampled_rows(B):
     """configs[3]: L = 32768, tree 64 + 4 masks (68 rows) and the 320-row layout, one layer of the
     Llama shape; the oracle evaluates a sample of rows (all heads) one by one."""
