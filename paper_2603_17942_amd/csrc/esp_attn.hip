@@ -4,16 +4,11 @@
 // in its ancestor bitset (held at slots len[b] + c).  Only the last n_rows keys of a sequence need
 // a mask test; every tile that lies inside the committed cache runs unmasked.
 //
-// bf16 / head_dim 128 path (k_attn_mfma): the G = n_q/n_kv query heads of a kv head times the
-// block rows form the "query columns" of a (keys x queries) problem.  A workgroup owns W*32 query
-// columns (W waves) and one split of the key range; K tiles ([64 keys][128]) and V tiles (already
-// slot-contiguous per feature in HBM, [128][64]) are staged through LDS with register
-// double-buffering and shared by the W waves.  S^T = K Q^T and O^T = V^T P^T both run on
-// v_mfma_f32_32x32x16_bf16: computing the transposed scores leaves each lane with one query
-// column and 16 keys per 32-key block, which is exactly the B-operand layout P^T needs, so the
-// probabilities never leave registers.  Online softmax in fp32 (base-2 exponent), one exchange
-// between the two lane halves per tile.  Partial (m, l, O) per split are merged by k_attn_merge in
-// split order (fixed, so results do not depend on scheduling).
+// bf16 / head_dim 128 path (k_attn_ring, described at its definition): the G = n_q/n_kv query heads
+// of a kv head times the block rows form the "query columns" of a (keys x queries) problem; a
+// workgroup owns the columns of one kv head and one split of the key range, and the per-split partial
+// (m, l, O) are merged by k_attn_merge_ring in split order (fixed, so results do not depend on
+// scheduling).
 //
 // Generic path (k_attn_generic): one wave per (row, head, split), any dtype / head_dim multiple of
 // 64; used by the fp32 tiny configuration.
@@ -110,8 +105,8 @@ __global__ __launch_bounds__(64) void k_attn_generic(BlockDev b, KvDev kv, int l
 // transposed scores leaves each lane with one query column and 16 keys per 32-key block, which is
 // exactly the B-operand layout P^T needs, so the probabilities never leave registers.  Online
 // softmax in fp32 (base-2 exponent), one exchange between the two lane halves per 32 keys.
-// Partial (m, l, O) per split are merged by k_attn_merge in split order (fixed, so results do not
-// depend on scheduling).
+// Partial (m, l, O) per split are merged by k_attn_merge_ring in split order (fixed, so results do
+// not depend on scheduling).
 constexpr int K_TILE_BYTES = 64 * 128 * 2;   // 64 keys: two cache blocks of 32 slots, 16 fragments of 1 KB
 constexpr int V_TILE_BYTES = 64 * 128 * 2;
 constexpr int RING_STAGES = 4;
