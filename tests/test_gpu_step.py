@@ -60,6 +60,7 @@ def compare_step(dec, res, blk_nodes, rows_per_seq, shape, kp, tol, logits_gpu, 
     of the oracle made an integer decision non-comparable (everything up to it was checked)."""
     R = res.logits.shape[0]
     err = rel_err_rows(logits_gpu[:R], res.logits)
+    print(f"  logits: worst row-wise relative error {err:.2e} (tolerance {tol:.0e})", flush=True)
     assert err <= tol, f"logits rel err {err}"
     g_gpu = dec.node_argmax[:blk_nodes].cpu().numpy()
     for r in range(blk_nodes):
