@@ -412,10 +412,10 @@ def test_config1_sampled_loop_is_lossless_and_matches_oracle(B, tiny_setup, layo
     dec.eng.close()
 
 
-@pytest.mark.parametrize("n_nodes,k", [(12, 2), (40, 4)])
+@pytest.mark.parametrize("n_nodes,k", [(12, 2), (40, 4), (160, 2)])
 def test_bf16_sampled_loop_is_lossless_up_to_near_ties(B, n_nodes, k):
     """bf16 path (noise in the LM-head GEMM's arg-max epilogue; 36 rows = one pass over the LM head
-    for all rows, 200 rows = gathered tree rows): the ESP loop with sampling on reproduces the same
+    for all rows, 200 rows = gathered tree rows, 160 tree rows = the large-tile kernel's epilogue): the ESP loop with sampling on reproduces the same
     path's one-token-at-a-time sampling; a token may differ only where the margin of the noisy
     arg-max is inside the bf16 band."""
     from paper_2603_17942_amd import decode
