@@ -464,6 +464,27 @@ def test_attn_tree_bf16_mfma(B, bf16_engine, n_nodes, k, layout, cache_lens):
 
 
 # ------------------------------------------------------------------------- mask initialisations
+@pytest.mark.parametrize("hq,hkv,n_nodes,k,layout,cache_lens", [
+    (2, 2, 40, 3, 0, [515]),            # no grouping: one query head per kv head
+    (8, 1, 30, 4, 0, [260, 31]),        # eight query heads share one kv head: 1200 query columns per kv head
+    (16, 2, 9, 2, 1, [70]),             # G = 8, few rows
+    (4, 4, 120, 4, 1, [1000, 64, 129, 5]),
+])
+def test_attn_tree_bf16_other_head_groupings(B, hq, hkv, n_nodes, k, layout, cache_lens):
+    """The MFMA attention kernel at other ratios of query to kv heads than the 4 of the two 8B shapes
+    (query columns of a kv head = block rows x group size: from 124 to 1200 here, i.e. one to four
+    workgroups per kv head and split, with and without paired waves)."""
+    shape = small_shape(d_model=max(hq * 16, 128), n_q_heads=hq, n_kv_heads=hkv, head_dim=128, d_ff=256, vocab=512, n_layers=1,
+                        dtype="bf16", qk_norm=False, rope_theta=1.0e4)
+    w = synth.make_weights(shape, seed=5)
+    rows = n_nodes * (k + 1) if layout == 0 else n_nodes + k
+    eng = B.Engine(shape, w, max_batch=len(cache_lens), max_rows_per_seq=rows, max_kv_len=max(cache_lens) + rows + 64)
+    print(f"attn bf16 hq={hq} hkv={hkv} n={n_nodes} k={k} layout={layout} L={cache_lens}", flush=True)
+    err = run_attention_case(B, shape, eng, n_nodes, k, layout, cache_lens, seed=90)
+    eng.close()
+    assert err < 2e-2
+
+
 @pytest.mark.parametrize("which", ["tiny", "bf16"])
 def test_mask_last_k_and_gaussian_inits(B, tiny_engine, bf16_engine, which):
     """Sec. 4 mask-design variants a (last k prompt tokens) and b (Gaussian fit of the embedding
